@@ -1,0 +1,137 @@
+/*
+ * libaj - judge-augmented verification of speculation windows on AMD MI355X (gfx950).
+ *
+ * One call verifies a batch of B speculation windows, each holding K draft
+ * tokens plus one bonus position (K+1 "verify rows" per window):
+ *
+ *   1. LM head     logit[r][v] = sum_k hidden_t[r][k] * W_lm[v][k]
+ *   2. greedy      t*[r] = lowest v attaining max_v logit[r][v]
+ *                  (greedy verification compares the draft tokens with the
+ *                   target's own next-token predictions: Section 2, footnote)
+ *   3. judge       slot j mismatches when t*[b][j] != draft_tok[b][j]; at a
+ *                  mismatch z = clf_w . [hidden_t[b][j+o] ; hidden_d[b][j+o]] + clf_b
+ *                  with o = feat_offset (1: the states that encode the draft
+ *                  token, Section 3.2 item 1 and Appendix B); the mismatch is
+ *                  accepted when sigmoid(z) < tau (Section 3.3: the classifier is
+ *                  called where the base algorithm would reject; an unimportant
+ *                  token is accepted and verification goes on)
+ *   4. scan        out_len[b] = first slot that mismatches and is not accepted
+ *                  (K if none); out_tok[b] = t*[b][out_len[b]]: the target's
+ *                  correction token, or the bonus token when out_len == K
+ *                  (Section 2: the first mismatching token and all after it are
+ *                  rejected).
+ *
+ * The B*(K+1) x V logits are never written to memory.  The threshold test is
+ * evaluated as z < log(tau/(1-tau)) (-inf / +inf at tau = 0 / 1), which equals
+ * sigmoid(z) < tau in real arithmetic and makes tau = 0 plain greedy
+ * speculative decoding and tau = 1 accept every draft token.
+ *
+ * Conventions
+ *   - All tensor arguments are DEVICE pointers owned by the caller, row-major,
+ *     16-byte aligned; clf_b and tau are host scalars.  The library keeps none
+ *     of them past the call.  Inputs must be finite.
+ *   - Calls are asynchronous on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream); outputs are valid once the stream has been
+ *     synchronised.  No host<->device copies, no host synchronisation.
+ *   - A handle owns a device workspace sized at aj_create; one handle = one
+ *     call in flight.  Different handles are independent.
+ *   - Every function returns AJ_OK (0) or a negative aj_status; nothing throws.
+ *     Draft tokens outside [0, V) are legal and simply never match.
+ */
+#ifndef AJ_H
+#define AJ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct aj_handle aj_handle; /* opaque */
+
+typedef enum { AJ_F32 = 0, AJ_BF16 = 1 } aj_dtype;
+
+typedef enum {
+    AJ_OK = 0,
+    AJ_EINVAL = -1,  /* null pointer, bad shape, tau outside [0,1] or NaN, misaligned pointer */
+    AJ_ENOMEM = -2,  /* workspace allocation failed */
+    AJ_EHIP = -3,    /* a HIP call failed; aj_last_hip_error() has the hipError_t */
+    AJ_ESTATE = -4   /* call not valid for this handle (e.g. debug data not enabled) */
+} aj_status;
+
+enum {
+    AJ_FLAG_DEBUG = 1,   /* keep per-slot judge scores for aj_debug_ptrs */
+    AJ_FLAG_PROFILE = 2  /* record HIP events around the LM-head kernel (aj_profile_read) */
+};
+
+/* LM-head kernel choice; AJ_KERNEL_AUTO picks by shape. The others force one for tests/benchmarks. */
+enum { AJ_KERNEL_AUTO = 0, AJ_KERNEL_TILE = 1, AJ_KERNEL_STREAM = 2, AJ_KERNEL_BIG = 3 };
+
+typedef struct {
+    int32_t B;           /* windows per call, >= 0 (0: the call does nothing) */
+    int32_t K;           /* draft tokens per window, 1 <= K <= 1023 */
+    int32_t d_t;         /* target hidden size; multiple of 8 (bf16) or 4 (f32) */
+    int32_t d_d;         /* draft hidden size; 0 = judge on target states only; same multiples */
+    int32_t V;           /* vocabulary size, >= 1 */
+    int32_t dtype;       /* aj_dtype of hidden_t, hidden_d, W_lm, clf_w */
+    int32_t feat_offset; /* 1 (default) or 0: the judge reads verify row j + feat_offset */
+    int32_t flags;       /* AJ_FLAG_* */
+    int32_t kernel;      /* AJ_KERNEL_* */
+} aj_config;
+
+/* Validate cfg, allocate the workspace on the current device. *out is NULL on failure. */
+int aj_create(const aj_config *cfg, aj_handle **out);
+
+/*
+ * Steps 1-4 (see the top of this file).
+ *   hidden_t  [B][K+1][d_t]   target final hidden states
+ *   hidden_d  [B][K+1][d_d]   draft final hidden states (may be NULL when d_d == 0)
+ *   W_lm      [V][d_t]        LM-head weight
+ *   draft_tok [B][K] int32
+ *   clf_w     [d_t + d_d]     judge weight, target part first
+ *   out_len   [B] int32       accepted draft tokens, in [0, K]
+ *   out_tok   [B] int32       emitted token, in [0, V)
+ * AJ_EINVAL on null / misaligned pointers or tau outside [0,1]; AJ_EHIP on a launch failure.
+ */
+int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_d, const void *W_lm,
+              const int32_t *draft_tok, const void *clf_w, float clf_b, float tau,
+              int32_t *out_len, int32_t *out_tok, void *stream);
+
+/* Frees the workspace. The caller must have synchronised any stream still using the handle. */
+int aj_destroy(aj_handle *h);
+
+/*
+ * Device pointers into the handle's workspace, valid after the stream of the last
+ * aj_verify has been synchronised and until the next call / aj_destroy:
+ *   t_star   [B*(K+1)] int32  greedy token of every verify row           (always kept)
+ *   maxlogit [B*(K+1)] float  its logit                                   (always kept)
+ *   score    [2][B][K] float  plane 0: judge logit z, plane 1: sigmoid(z) = P(important), at
+ *                             mismatching slots; NaN at matching ones
+ *                             (AJ_FLAG_DEBUG only, else AJ_ESTATE if requested)
+ * Any of the three out-pointers may be NULL.
+ */
+int aj_debug_ptrs(aj_handle *h, const int32_t **t_star, const float **maxlogit, const float **score);
+
+/*
+ * Debug: step 1 alone, writing all logits [B*(K+1)][V] as float to device memory
+ * `logits` (the product path never does this). Uses the same kernels as aj_verify.
+ */
+int aj_debug_logits(aj_handle *h, const void *hidden_t, const void *W_lm, float *logits, void *stream);
+
+/*
+ * AJ_FLAG_PROFILE: synchronises the events of the most recent calls (at most 64 are
+ * kept) and writes the LM-head kernel's duration of each, oldest first, in
+ * milliseconds; *n in: capacity of ms, out: count written.
+ */
+int aj_profile_read(aj_handle *h, float *ms, int32_t *n);
+
+/* Name of the LM-head kernel variant this handle dispatches to (static string). */
+const char *aj_kernel_name(const aj_handle *h);
+
+const char *aj_strerror(int status);
+int aj_last_hip_error(void); /* hipError_t of the last AJ_EHIP on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AJ_H */

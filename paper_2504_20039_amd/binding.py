@@ -1,0 +1,183 @@
+"""ctypes binding of libaj.so: same names as the C ABI, argument marshalling only.
+
+PyTorch supplies device memory (``tensor.data_ptr()``) and streams
+(``torch.cuda.current_stream().cuda_stream``); every step of the path runs in the library's
+kernels.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libaj.so")
+
+AJ_F32, AJ_BF16 = 0, 1
+AJ_FLAG_DEBUG, AJ_FLAG_PROFILE = 1, 2
+AJ_KERNEL_AUTO, AJ_KERNEL_TILE, AJ_KERNEL_STREAM, AJ_KERNEL_BIG = 0, 1, 2, 3
+
+SYMBOLS = ["aj_create", "aj_verify", "aj_destroy", "aj_debug_ptrs", "aj_debug_logits",
+           "aj_profile_read", "aj_kernel_name", "aj_strerror", "aj_last_hip_error"]
+
+
+class AjError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {aj_strerror(status)} (status {status})")
+
+
+class _Config(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("B", "K", "d_t", "d_d", "V", "dtype", "feat_offset", "flags", "kernel")]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libaj.so (built in-tree by ``paper_2504_20039_amd.build``). Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is not built: run `python -m paper_2504_20039_amd.build` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float
+    lib.aj_create.argtypes = [ctypes.POINTER(_Config), ctypes.POINTER(vp)]
+    lib.aj_create.restype = ctypes.c_int
+    lib.aj_verify.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, vp, vp, vp]
+    lib.aj_verify.restype = ctypes.c_int
+    lib.aj_destroy.argtypes = [vp]
+    lib.aj_destroy.restype = ctypes.c_int
+    lib.aj_debug_ptrs.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp)]
+    lib.aj_debug_ptrs.restype = ctypes.c_int
+    lib.aj_debug_logits.argtypes = [vp, vp, vp, vp, vp]
+    lib.aj_debug_logits.restype = ctypes.c_int
+    lib.aj_profile_read.argtypes = [vp, ctypes.POINTER(f32), ctypes.POINTER(i32)]
+    lib.aj_profile_read.restype = ctypes.c_int
+    lib.aj_kernel_name.argtypes = [vp]
+    lib.aj_kernel_name.restype = ctypes.c_char_p
+    lib.aj_strerror.argtypes = [ctypes.c_int]
+    lib.aj_strerror.restype = ctypes.c_char_p
+    lib.aj_last_hip_error.argtypes = []
+    lib.aj_last_hip_error.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def exported_symbols():
+    """Names from include/aj.h that the loaded library exports."""
+    lib = load_library()
+    return [s for s in SYMBOLS if hasattr(lib, s)]
+
+
+def aj_strerror(status: int) -> str:
+    return load_library().aj_strerror(int(status)).decode()
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda:
+        raise ValueError("libaj takes device tensors")
+    if not t.is_contiguous():
+        raise ValueError("libaj takes contiguous row-major tensors")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def aj_create(B, K, d_t, d_d, V, dtype=AJ_BF16, feat_offset=1, flags=0, kernel=AJ_KERNEL_AUTO):
+    cfg = _Config(B, K, d_t, d_d, V, dtype, feat_offset, flags, kernel)
+    h = ctypes.c_void_p()
+    rc = load_library().aj_create(ctypes.byref(cfg), ctypes.byref(h))
+    if rc != 0:
+        raise AjError(rc, "aj_create")
+    return h
+
+
+def aj_verify(h, hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, out_len, out_tok, stream=None):
+    rc = load_library().aj_verify(h, _ptr(hidden_t), _ptr(hidden_d), _ptr(W_lm), _ptr(draft_tok),
+                                  _ptr(clf_w), float(clf_b), float(tau), _ptr(out_len), _ptr(out_tok),
+                                  _stream(stream))
+    if rc != 0:
+        raise AjError(rc, "aj_verify")
+
+
+def aj_destroy(h):
+    rc = load_library().aj_destroy(h)
+    if rc != 0:
+        raise AjError(rc, "aj_destroy")
+
+
+def aj_kernel_name(h) -> str:
+    return load_library().aj_kernel_name(h).decode()
+
+
+def _copy_from_device(ptr: int, shape, dtype) -> np.ndarray:
+    out = np.empty(shape, dtype=dtype)
+    if out.nbytes == 0 or not ptr:
+        return out
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+    hip.hipMemcpy.restype = ctypes.c_int
+    rc = hip.hipMemcpy(out.ctypes.data, ptr, out.nbytes, 2)   # hipMemcpyDeviceToHost
+    if rc != 0:
+        raise RuntimeError(f"hipMemcpy failed with hipError {rc}")
+    return out
+
+
+def aj_debug_ptrs(h, B, K, want_score=True):
+    """Host copies (t_star int32 [B*(K+1)], maxlogit f32 [B*(K+1)], score f32 [2,B,K] or None).
+
+    The caller synchronises the stream of the last aj_verify first.
+    """
+    t, m, s = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+    rc = load_library().aj_debug_ptrs(h, ctypes.byref(t), ctypes.byref(m),
+                                      ctypes.byref(s) if want_score else None)
+    if rc != 0:
+        raise AjError(rc, "aj_debug_ptrs")
+    M = B * (K + 1)
+    t_star = _copy_from_device(t.value, (M,), np.int32)
+    maxlogit = _copy_from_device(m.value, (M,), np.float32)
+    score = _copy_from_device(s.value, (2, B, K), np.float32) if want_score else None
+    return t_star, maxlogit, score
+
+
+def aj_debug_logits(h, hidden_t, W_lm, logits, stream=None):
+    rc = load_library().aj_debug_logits(h, _ptr(hidden_t), _ptr(W_lm), _ptr(logits), _stream(stream))
+    if rc != 0:
+        raise AjError(rc, "aj_debug_logits")
+
+
+def aj_profile_read(h, capacity=64):
+    ms = (ctypes.c_float * capacity)()
+    n = ctypes.c_int32(capacity)
+    rc = load_library().aj_profile_read(h, ms, ctypes.byref(n))
+    if rc != 0:
+        raise AjError(rc, "aj_profile_read")
+    return [float(ms[i]) for i in range(n.value)]
+
+
+def device_tensor(a: np.ndarray, device="cuda:0"):
+    """Upload a stored numpy tensor (uint16 = bf16 bits, float32, int32) without changing a bit."""
+    import torch
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)

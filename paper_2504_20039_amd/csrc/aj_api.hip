@@ -1,0 +1,246 @@
+// C ABI of libaj (declared in include/aj.h): argument checks, workspace, kernel dispatch.
+#include <math.h>
+#include <new>
+
+#include "../../include/aj.h"
+#include "aj_internal.h"
+
+using namespace aj;
+
+struct aj_handle {
+    aj_config cfg;
+    int M;
+    int variant;   // AJ_KERNEL_* actually used (for bf16), or -1 for the fp32 kernel
+    int nblocks;   // partials per verify row
+    int device;
+    float *pval;
+    int32_t *pidx;
+    int32_t *t_star;
+    float *maxlogit;
+    float *score;  // [2][B][K] or nullptr
+    hipEvent_t ev[64][2];
+    bool ev_ok;
+    uint64_t calls;
+};
+
+static thread_local int g_last_hip = 0;
+
+static int hip_fail(hipError_t e)
+{
+    g_last_hip = (int)e;
+    return AJ_EHIP;
+}
+
+extern "C" int aj_last_hip_error(void) { return g_last_hip; }
+
+extern "C" const char *aj_strerror(int status)
+{
+    switch (status) {
+        case AJ_OK: return "ok";
+        case AJ_EINVAL: return "invalid argument (null/misaligned pointer, bad shape, or tau outside [0,1])";
+        case AJ_ENOMEM: return "device workspace allocation failed";
+        case AJ_EHIP: return "a HIP call failed (see aj_last_hip_error)";
+        case AJ_ESTATE: return "call not valid for this handle";
+        default: return "unknown status";
+    }
+}
+
+static bool aligned16(const void *p) { return (((uintptr_t)p) & 15u) == 0; }
+
+static void free_all(aj_handle *h)
+{
+    if (h->pval) (void)hipFree(h->pval);
+    if (h->pidx) (void)hipFree(h->pidx);
+    if (h->t_star) (void)hipFree(h->t_star);
+    if (h->maxlogit) (void)hipFree(h->maxlogit);
+    if (h->score) (void)hipFree(h->score);
+    if (h->ev_ok)
+        for (int i = 0; i < 64; ++i) {
+            (void)hipEventDestroy(h->ev[i][0]);
+            (void)hipEventDestroy(h->ev[i][1]);
+        }
+}
+
+extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
+{
+    if (out) *out = nullptr;
+    if (!cfg || !out) return AJ_EINVAL;
+    const aj_config &c = *cfg;
+    if (c.dtype != AJ_F32 && c.dtype != AJ_BF16) return AJ_EINVAL;
+    const int mult = c.dtype == AJ_BF16 ? 8 : 4;
+    if (c.B < 0 || c.K < 1 || c.K > 1023 || c.V < 1 || c.d_t < mult || c.d_d < 0) return AJ_EINVAL;
+    if (c.d_t % mult || c.d_d % mult) return AJ_EINVAL;
+    if (c.feat_offset != 0 && c.feat_offset != 1) return AJ_EINVAL;
+    if (c.kernel < AJ_KERNEL_AUTO || c.kernel > AJ_KERNEL_BIG) return AJ_EINVAL;
+    if ((int64_t)c.B * (c.K + 1) > (int64_t)1 << 24) return AJ_EINVAL;
+
+    aj_handle *h = new (std::nothrow) aj_handle();
+    if (!h) return AJ_ENOMEM;
+    h->cfg = c;
+    h->M = c.B * (c.K + 1);
+    hipError_t e = hipGetDevice(&h->device);
+    if (e != hipSuccess) {
+        delete h;
+        return hip_fail(e);
+    }
+    if (c.dtype == AJ_F32) {
+        h->variant = -1;
+        h->nblocks = lm_head_f32_blocks(c.V);
+    } else {
+        h->variant = AJ_KERNEL_TILE;
+        h->nblocks = lm_head_tile_blocks(c.V);
+    }
+    if (h->M > 0) {
+        const size_t np = (size_t)h->nblocks * h->M;
+        bool ok = hipMalloc(&h->pval, np * sizeof(float)) == hipSuccess &&
+                  hipMalloc(&h->pidx, np * sizeof(int32_t)) == hipSuccess &&
+                  hipMalloc(&h->t_star, (size_t)h->M * sizeof(int32_t)) == hipSuccess &&
+                  hipMalloc(&h->maxlogit, (size_t)h->M * sizeof(float)) == hipSuccess;
+        if (ok && (c.flags & AJ_FLAG_DEBUG))
+            ok = hipMalloc(&h->score, (size_t)2 * c.B * c.K * sizeof(float)) == hipSuccess;
+        if (!ok) {
+            (void)hipGetLastError();
+            free_all(h);
+            delete h;
+            return AJ_ENOMEM;
+        }
+    }
+    if (c.flags & AJ_FLAG_PROFILE) {
+        h->ev_ok = true;
+        for (int i = 0; i < 64; ++i)
+            for (int j = 0; j < 2; ++j) {
+                e = hipEventCreate(&h->ev[i][j]);
+                if (e != hipSuccess) {   // destroy what exists, then fail
+                    for (int ii = 0; ii <= i; ++ii)
+                        for (int jj = 0; jj < (ii == i ? j : 2); ++jj) (void)hipEventDestroy(h->ev[ii][jj]);
+                    h->ev_ok = false;
+                    free_all(h);
+                    delete h;
+                    return hip_fail(e);
+                }
+            }
+    }
+    *out = h;
+    return AJ_OK;
+}
+
+extern "C" int aj_destroy(aj_handle *h)
+{
+    if (!h) return AJ_EINVAL;
+    free_all(h);
+    delete h;
+    return AJ_OK;
+}
+
+static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void *W_lm, float *dump, hipStream_t s)
+{
+    LmHeadArgs a;
+    a.H = hidden_t;
+    a.W = W_lm;
+    a.M = h->M;
+    a.V = h->cfg.V;
+    a.d = h->cfg.d_t;
+    a.pval = h->pval;
+    a.pidx = h->pidx;
+    a.dump = dump;
+    if (h->variant < 0) return lm_head_f32(a, s);
+    return lm_head_tile_bf16(a, s);
+}
+
+extern "C" int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_d, const void *W_lm,
+                         const int32_t *draft_tok, const void *clf_w, float clf_b, float tau,
+                         int32_t *out_len, int32_t *out_tok, void *stream)
+{
+    if (!h) return AJ_EINVAL;
+    if (!(tau >= 0.f && tau <= 1.f)) return AJ_EINVAL;   // also refuses NaN
+    if (!isfinite(clf_b)) return AJ_EINVAL;
+    if (h->M == 0) return AJ_OK;
+    const aj_config &c = h->cfg;
+    if (!hidden_t || !W_lm || !draft_tok || !clf_w || !out_len || !out_tok) return AJ_EINVAL;
+    if (c.d_d > 0 && !hidden_d) return AJ_EINVAL;
+    if (!aligned16(hidden_t) || !aligned16(W_lm) || !aligned16(clf_w) || (c.d_d > 0 && !aligned16(hidden_d)))
+        return AJ_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+
+    const bool prof = h->ev_ok;
+    const int slot = (int)(h->calls % 64);
+    hipError_t e;
+    if (prof && (e = hipEventRecord(h->ev[slot][0], s)) != hipSuccess) return hip_fail(e);
+    if ((e = launch_lm_head(h, hidden_t, W_lm, nullptr, s)) != hipSuccess) return hip_fail(e);
+    if (prof && (e = hipEventRecord(h->ev[slot][1], s)) != hipSuccess) return hip_fail(e);
+    if (prof) h->calls++;
+
+    TailArgs t;
+    t.hidden_t = hidden_t;
+    t.hidden_d = hidden_d;
+    t.clf_w = clf_w;
+    t.draft_tok = draft_tok;
+    t.pval = h->pval;
+    t.pidx = h->pidx;
+    t.nblocks = h->nblocks;
+    t.B = c.B;
+    t.K = c.K;
+    t.d_t = c.d_t;
+    t.d_d = c.d_d;
+    t.V = c.V;
+    t.dtype = c.dtype;
+    t.feat_offset = c.feat_offset;
+    t.clf_b = clf_b;
+    // threshold in logit space, computed in double from the float tau, rounded once to float
+    t.zthr = tau <= 0.f ? -INFINITY : (tau >= 1.f ? INFINITY : (float)log((double)tau / (1.0 - (double)tau)));
+    t.t_star = h->t_star;
+    t.maxlogit = h->maxlogit;
+    t.score = h->score;
+    t.out_len = out_len;
+    t.out_tok = out_tok;
+    if ((e = argmax_reduce(t, s)) != hipSuccess) return hip_fail(e);
+    if ((e = judge_scan(t, s)) != hipSuccess) return hip_fail(e);
+    return AJ_OK;
+}
+
+extern "C" int aj_debug_ptrs(aj_handle *h, const int32_t **t_star, const float **maxlogit, const float **score)
+{
+    if (!h) return AJ_EINVAL;
+    if (score && !h->score && h->M > 0) return AJ_ESTATE;
+    if (t_star) *t_star = h->t_star;
+    if (maxlogit) *maxlogit = h->maxlogit;
+    if (score) *score = h->score;
+    return AJ_OK;
+}
+
+extern "C" int aj_debug_logits(aj_handle *h, const void *hidden_t, const void *W_lm, float *logits, void *stream)
+{
+    if (!h) return AJ_EINVAL;
+    if (h->M == 0) return AJ_OK;
+    if (!hidden_t || !W_lm || !logits || !aligned16(hidden_t) || !aligned16(W_lm)) return AJ_EINVAL;
+    hipError_t e = launch_lm_head(h, hidden_t, W_lm, logits, (hipStream_t)stream);
+    return e == hipSuccess ? AJ_OK : hip_fail(e);
+}
+
+extern "C" int aj_profile_read(aj_handle *h, float *ms, int32_t *n)
+{
+    if (!h || !ms || !n || *n < 0) return AJ_EINVAL;
+    if (!h->ev_ok) return AJ_ESTATE;
+    const uint64_t have = h->calls < 64 ? h->calls : 64;
+    const int want = (int)((uint64_t)*n < have ? (uint64_t)*n : have);
+    for (int i = 0; i < want; ++i) {
+        const int slot = (int)((h->calls - want + i) % 64);
+        hipError_t e = hipEventSynchronize(h->ev[slot][1]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms[i], h->ev[slot][0], h->ev[slot][1]);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    *n = want;
+    return AJ_OK;
+}
+
+extern "C" const char *aj_kernel_name(const aj_handle *h)
+{
+    if (!h) return "none";
+    switch (h->variant) {
+        case -1: return "lm_head_f32";
+        case AJ_KERNEL_TILE: return "lm_head_tile_bf16";
+        case AJ_KERNEL_STREAM: return "lm_head_stream_bf16";
+        case AJ_KERNEL_BIG: return "lm_head_big_bf16";
+        default: return "unknown";
+    }
+}
