@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark of the judge-augmented verification step (aj_verify) on one MI355X.
+
+A step = one aj_verify call (LM head + greedy argmax + judge + first-reject scan) over one batch of
+seeded synthetic speculation windows already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+RIDGE = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # flop per byte
+
+
+def algorithmic(w, nblocks_bytes=0):
+    """Bytes and flops of one LM-head launch: W_lm and hidden_t read once, logits never stored."""
+    byts = w.V * w.d_t * w.elem_bytes + w.M * w.d_t * w.elem_bytes
+    flops = 2.0 * w.M * w.V * w.d_t
+    return byts, flops
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="8b_b1_k16")
+    ap.add_argument("--seed", type=int, default=None)
+    ap.add_argument("--kernel", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as wl
+    import paper_2504_20039_amd as aj
+
+    w = wl.WORKLOADS[args.workload]
+    seed = wl.DEFAULT_SEED if args.seed is None else args.seed
+    torch.cuda.set_device(0)
+
+    # ---- inputs (seeded, synthetic), uploaded once
+    ht, hd, W, cw = wl.hidden_t(w, seed), wl.hidden_d(w, seed), wl.w_lm(w, seed), wl.clf_w(w, seed)
+    d_ht, d_hd, d_W, d_cw = (aj.device_tensor(a) for a in (ht, hd, W, cw))
+    out_len = torch.zeros(w.B, dtype=torch.int32, device="cuda")
+    out_tok = torch.zeros(w.B, dtype=torch.int32, device="cuda")
+    h = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, w.dtype_code, 1, 0, args.kernel)
+    hp = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, w.dtype_code, 1, aj.AJ_FLAG_PROFILE, args.kernel)
+    # draft tokens follow the workload recipe relative to the target's greedy tokens; those come
+    # from a first (untimed) call of the library itself, with a placeholder draft
+    d_draft = torch.zeros((w.B, w.K), dtype=torch.int32, device="cuda")
+    aj.aj_verify(h, d_ht, d_hd, d_W, d_draft, d_cw, w.clf_b, w.tau, out_len, out_tok)
+    torch.cuda.synchronize()
+    t_star, _, _ = aj.aj_debug_ptrs(h, w.B, w.K, want_score=False)
+    draft = wl.draft_tokens(w, seed, t_star)
+    d_draft.copy_(torch.from_numpy(draft))
+
+    def step(handle):
+        aj.aj_verify(handle, d_ht, d_hd, d_W, d_draft, d_cw, w.clf_b, w.tau, out_len, out_tok)
+
+    for _ in range(args.warmup):
+        step(h)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(h)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    accepted = out_len.cpu().numpy().astype(np.int64)
+
+    # ---- the LM-head kernel alone: HIP events recorded by the library on the launch stream
+    k1 = []
+    n_prof = min(args.steps, 64)
+    for _ in range(min(args.warmup, 3)):
+        step(hp)
+    torch.cuda.synchronize()
+    for _ in range(n_prof):
+        step(hp)
+    torch.cuda.synchronize()
+    k1 = aj.aj_profile_read(hp, n_prof)
+    k1_ms = sum(k1) / len(k1)
+    kernel_name = aj.aj_kernel_name(h)
+
+    byts, flops = algorithmic(w)
+    intensity = flops / byts
+    if intensity < RIDGE:
+        roof = dict(bound="hbm", achieved=byts / (k1_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
+    else:
+        roof = dict(bound="mfma", achieved=flops / (k1_ms * 1e-3) / 1e12, peak=MFMA_BF16_PEAK_TFLOPS,
+                    unit="TFLOP/s")
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    tr_path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tr_path):
+        tr = json.load(open(tr_path)).get(f"{w.name}:{kernel_name}")
+        if tr:
+            roof["traffic"] = tr["bytes_per_launch"]
+    roof.update(kernel=kernel_name, kernel_ms=k1_ms, kernel_ms_median=statistics.median(k1),
+                algorithmic_bytes=byts, algorithmic_flops=flops,
+                hbm_gbs=byts / (k1_ms * 1e-3) / 1e9, mfma_tflops=flops / (k1_ms * 1e-3) / 1e12)
+
+    result = {
+        "metric": "verified spec windows/sec (LM-head+argmax+judge) at 1 GPU",
+        "value": w.B / (ms_per_step * 1e-3),
+        "unit": "windows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "K": w.K, "d_t": w.d_t, "d_d": w.d_d, "V": w.V,
+                   "verify_rows": w.M, "tau": w.tau, "p_match": w.p_match, "seed": seed},
+        "verify_rows_per_s": w.M / (ms_per_step * 1e-3),
+        "emitted_tokens_per_s": float((accepted + 1).sum()) / (ms_per_step * 1e-3),
+        "mean_accepted_len": float(accepted.mean()),
+        "roofline": roof,
+    }
+
+    # ---- the CPU oracle on the machine's host cores: a reported baseline, not the target
+    if not args.no_cpu_baseline:
+        import oracle
+        nwin = min(w.B, max(1, int(2.0e11 // (w.K + 1) // (w.V * w.d_t))))   # <= ~2e11 MACs
+        R = w.K + 1
+        reps = 3 if nwin * R * w.V * w.d_t < 3e10 else 1
+        times = []
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            ref = oracle.verify(ht[:nwin * R], hd[:nwin * R], W, draft[:nwin], cw, w.clf_b, w.tau)
+            times.append(time.perf_counter() - t0)
+        sec = statistics.median(times)
+        gl, gt = out_len.cpu().numpy()[:nwin], out_tok.cpu().numpy()[:nwin]
+        result["cpu_baseline"] = {
+            "value": nwin / sec, "unit": "windows/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {nwin} of {w.B} windows ({nwin * R} verify rows, full vocabulary), "
+                      f"steps 1-4, median of {reps} run(s), {sec:.2f} s each",
+            "sample_matches_gpu": bool(np.array_equal(gl, ref.out_len) and np.array_equal(gt, ref.out_tok)),
+        }
+    aj.aj_destroy(h)
+    aj.aj_destroy(hp)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
