@@ -64,7 +64,7 @@ def main():
     d_draft = torch.zeros((w.B, w.K), dtype=torch.int32, device="cuda")
     aj.aj_verify(h, d_ht, d_hd, d_W, d_draft, d_cw, w.clf_b, w.tau, out_len, out_tok)
     torch.cuda.synchronize()
-    t_star, _, _ = aj.aj_debug_ptrs(h, w.B, w.K, want_score=False)
+    t_star, _, _ = aj.aj_debug_copy(h, w.B, w.K, want_score=False)
     draft = wl.draft_tokens(w, seed, t_star)
     d_draft.copy_(torch.from_numpy(draft))
 

@@ -113,6 +113,12 @@ int aj_destroy(aj_handle *h);
 int aj_debug_ptrs(aj_handle *h, const int32_t **t_star, const float **maxlogit, const float **score);
 
 /*
+ * Same data copied to HOST arrays of the sizes above (NULL to skip one). Synchronises `stream`
+ * (the one of the last aj_verify) first, then copies synchronously.
+ */
+int aj_debug_copy(aj_handle *h, int32_t *t_star_host, float *maxlogit_host, float *score_host, void *stream);
+
+/*
  * Debug: step 1 alone, writing all logits [B*(K+1)][V] as float to device memory
  * `logits` (the product path never does this). Uses the same kernels as aj_verify.
  */

@@ -18,7 +18,7 @@ AJ_F32, AJ_BF16 = 0, 1
 AJ_FLAG_DEBUG, AJ_FLAG_PROFILE = 1, 2
 AJ_KERNEL_AUTO, AJ_KERNEL_TILE, AJ_KERNEL_STREAM, AJ_KERNEL_BIG = 0, 1, 2, 3
 
-SYMBOLS = ["aj_create", "aj_verify", "aj_destroy", "aj_debug_ptrs", "aj_debug_logits",
+SYMBOLS = ["aj_create", "aj_verify", "aj_destroy", "aj_debug_ptrs", "aj_debug_copy", "aj_debug_logits",
            "aj_profile_read", "aj_kernel_name", "aj_strerror", "aj_last_hip_error"]
 
 
@@ -48,6 +48,9 @@ def load_library():
     if not os.path.exists(_LIB_PATH):
         raise ImportError(f"{_LIB_PATH} is not built: run `python -m paper_2504_20039_amd.build` "
                           "(there is no fallback path)")
+    # torch ships its own HIP runtime (same soname as the system one); import it first so that
+    # libaj.so binds to that copy instead of bringing a second runtime into the process
+    import torch  # noqa: F401
     lib = ctypes.CDLL(_LIB_PATH)
     vp, i32, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float
     lib.aj_create.argtypes = [ctypes.POINTER(_Config), ctypes.POINTER(vp)]
@@ -58,6 +61,8 @@ def load_library():
     lib.aj_destroy.restype = ctypes.c_int
     lib.aj_debug_ptrs.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp)]
     lib.aj_debug_ptrs.restype = ctypes.c_int
+    lib.aj_debug_copy.argtypes = [vp, vp, vp, vp, vp]
+    lib.aj_debug_copy.restype = ctypes.c_int
     lib.aj_debug_logits.argtypes = [vp, vp, vp, vp, vp]
     lib.aj_debug_logits.restype = ctypes.c_int
     lib.aj_profile_read.argtypes = [vp, ctypes.POINTER(f32), ctypes.POINTER(i32)]
@@ -130,33 +135,26 @@ def aj_kernel_name(h) -> str:
     return load_library().aj_kernel_name(h).decode()
 
 
-def _copy_from_device(ptr: int, shape, dtype) -> np.ndarray:
-    out = np.empty(shape, dtype=dtype)
-    if out.nbytes == 0 or not ptr:
-        return out
-    hip = ctypes.CDLL("libamdhip64.so")
-    hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
-    hip.hipMemcpy.restype = ctypes.c_int
-    rc = hip.hipMemcpy(out.ctypes.data, ptr, out.nbytes, 2)   # hipMemcpyDeviceToHost
-    if rc != 0:
-        raise RuntimeError(f"hipMemcpy failed with hipError {rc}")
-    return out
-
-
-def aj_debug_ptrs(h, B, K, want_score=True):
-    """Host copies (t_star int32 [B*(K+1)], maxlogit f32 [B*(K+1)], score f32 [2,B,K] or None).
-
-    The caller synchronises the stream of the last aj_verify first.
-    """
+def aj_debug_ptrs(h):
+    """Raw device addresses (t_star, maxlogit, score-or-None) inside the handle's workspace."""
     t, m, s = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
-    rc = load_library().aj_debug_ptrs(h, ctypes.byref(t), ctypes.byref(m),
-                                      ctypes.byref(s) if want_score else None)
+    rc = load_library().aj_debug_ptrs(h, ctypes.byref(t), ctypes.byref(m), None)
     if rc != 0:
         raise AjError(rc, "aj_debug_ptrs")
+    rc = load_library().aj_debug_ptrs(h, None, None, ctypes.byref(s))
+    return t.value, m.value, (s.value if rc == 0 else None)
+
+
+def aj_debug_copy(h, B, K, want_score=True, stream=None):
+    """Host copies (t_star int32 [B*(K+1)], maxlogit f32 [B*(K+1)], score f32 [2,B,K] or None)."""
     M = B * (K + 1)
-    t_star = _copy_from_device(t.value, (M,), np.int32)
-    maxlogit = _copy_from_device(m.value, (M,), np.float32)
-    score = _copy_from_device(s.value, (2, B, K), np.float32) if want_score else None
+    t_star = np.empty(M, np.int32)
+    maxlogit = np.empty(M, np.float32)
+    score = np.empty((2, B, K), np.float32) if want_score else None
+    rc = load_library().aj_debug_copy(h, t_star.ctypes.data, maxlogit.ctypes.data,
+                                      score.ctypes.data if want_score else None, _stream(stream))
+    if rc != 0:
+        raise AjError(rc, "aj_debug_copy")
     return t_star, maxlogit, score
 
 

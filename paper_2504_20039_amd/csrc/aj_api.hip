@@ -208,6 +208,22 @@ extern "C" int aj_debug_ptrs(aj_handle *h, const int32_t **t_star, const float *
     return AJ_OK;
 }
 
+extern "C" int aj_debug_copy(aj_handle *h, int32_t *t_star_host, float *maxlogit_host, float *score_host,
+                             void *stream)
+{
+    if (!h) return AJ_EINVAL;
+    if (score_host && !h->score && h->M > 0) return AJ_ESTATE;
+    if (h->M == 0) return AJ_OK;
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e == hipSuccess && t_star_host)
+        e = hipMemcpy(t_star_host, h->t_star, (size_t)h->M * sizeof(int32_t), hipMemcpyDeviceToHost);
+    if (e == hipSuccess && maxlogit_host)
+        e = hipMemcpy(maxlogit_host, h->maxlogit, (size_t)h->M * sizeof(float), hipMemcpyDeviceToHost);
+    if (e == hipSuccess && score_host)
+        e = hipMemcpy(score_host, h->score, (size_t)2 * h->cfg.B * h->cfg.K * sizeof(float), hipMemcpyDeviceToHost);
+    return e == hipSuccess ? AJ_OK : hip_fail(e);
+}
+
 extern "C" int aj_debug_logits(aj_handle *h, const void *hidden_t, const void *W_lm, float *logits, void *stream)
 {
     if (!h) return AJ_EINVAL;

@@ -98,7 +98,7 @@ def run_gpu(x, draft, tau, feat_offset=1, kernel=0, clf_b=None, flags=None, repe
             aj.aj_verify(h, dev[0], dev[1] if w.d_d > 0 else None, dev[2], dev[3], dev[4], clf_b, tau,
                          out_len, out_tok)
             torch.cuda.synchronize()
-            t_star, maxlogit, score = aj.aj_debug_ptrs(h, w.B, w.K, want_score=bool(flags & aj.AJ_FLAG_DEBUG))
+            t_star, maxlogit, score = aj.aj_debug_copy(h, w.B, w.K, want_score=bool(flags & aj.AJ_FLAG_DEBUG))
             outs.append(dict(out_len=out_len.cpu().numpy()[:w.B].copy(), out_tok=out_tok.cpu().numpy()[:w.B].copy(),
                              t_star=t_star, maxlogit=maxlogit, score=score, kernel=name))
     finally:

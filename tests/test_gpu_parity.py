@@ -169,7 +169,7 @@ def test_empty_batch_and_bad_calls():
     with pytest.raises(aj.AjError):
         aj.aj_verify(h, z[1:], z, W, i, z, 0.0, 0.5, i, i)              # misaligned
     with pytest.raises(aj.AjError):
-        aj.aj_debug_ptrs(h, 1, 8, want_score=True)                      # AJ_FLAG_DEBUG not set
+        aj.aj_debug_copy(h, 1, 8, want_score=True)                      # AJ_FLAG_DEBUG not set
     aj.aj_destroy(h)
 
 
