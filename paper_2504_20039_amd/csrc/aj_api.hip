@@ -13,8 +13,8 @@ struct aj_handle {
     int variant;   // AJ_KERNEL_* actually used (for bf16), or -1 for the fp32 kernel
     int nblocks;   // partials per verify row
     int device;
-    float *pval;
-    int32_t *pidx;
+    int num_cus;
+    Best *part;    // [M][nblocks]
     int32_t *t_star;
     float *maxlogit;
     float *score;  // [2][B][K] or nullptr
@@ -49,8 +49,7 @@ static bool aligned16(const void *p) { return (((uintptr_t)p) & 15u) == 0; }
 
 static void free_all(aj_handle *h)
 {
-    if (h->pval) (void)hipFree(h->pval);
-    if (h->pidx) (void)hipFree(h->pidx);
+    if (h->part) (void)hipFree(h->part);
     if (h->t_star) (void)hipFree(h->t_star);
     if (h->maxlogit) (void)hipFree(h->maxlogit);
     if (h->score) (void)hipFree(h->score);
@@ -83,17 +82,36 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
         delete h;
         return hip_fail(e);
     }
+    e = hipDeviceGetAttribute(&h->num_cus, hipDeviceAttributeMultiprocessorCount, h->device);
+    if (e != hipSuccess) {
+        delete h;
+        return hip_fail(e);
+    }
     if (c.dtype == AJ_F32) {
+        if (c.kernel != AJ_KERNEL_AUTO) {
+            delete h;
+            return AJ_EINVAL;
+        }
         h->variant = -1;
         h->nblocks = lm_head_f32_blocks(c.V);
     } else {
-        h->variant = AJ_KERNEL_TILE;
-        h->nblocks = lm_head_tile_blocks(c.V);
+        int v = c.kernel;
+        if (v == AJ_KERNEL_AUTO) {
+            // W_lm-streaming regime while one 32-row block holds every verify row; the large-tile
+            // kernel once the rows fill a good part of its 256-row tile; the general kernel otherwise
+            if (lm_head_mfma_supports(AJ_KERNEL_STREAM, h->M, c.V, c.d_t)) v = AJ_KERNEL_STREAM;
+            else if (h->M >= 192 && lm_head_mfma_supports(AJ_KERNEL_BIG, h->M, c.V, c.d_t)) v = AJ_KERNEL_BIG;
+            else v = AJ_KERNEL_TILE;
+        } else if (v != AJ_KERNEL_TILE && h->M > 0 && !lm_head_mfma_supports(v, h->M, c.V, c.d_t)) {
+            delete h;
+            return AJ_EINVAL;   // a forced variant that cannot run this shape
+        }
+        h->variant = v;
+        h->nblocks = v == AJ_KERNEL_TILE ? lm_head_tile_blocks(c.V) : lm_head_mfma_blocks(v, c.V);
     }
     if (h->M > 0) {
         const size_t np = (size_t)h->nblocks * h->M;
-        bool ok = hipMalloc(&h->pval, np * sizeof(float)) == hipSuccess &&
-                  hipMalloc(&h->pidx, np * sizeof(int32_t)) == hipSuccess &&
+        bool ok = hipMalloc(&h->part, np * sizeof(Best)) == hipSuccess &&
                   hipMalloc(&h->t_star, (size_t)h->M * sizeof(int32_t)) == hipSuccess &&
                   hipMalloc(&h->maxlogit, (size_t)h->M * sizeof(float)) == hipSuccess;
         if (ok && (c.flags & AJ_FLAG_DEBUG))
@@ -140,11 +158,12 @@ static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void 
     a.M = h->M;
     a.V = h->cfg.V;
     a.d = h->cfg.d_t;
-    a.pval = h->pval;
-    a.pidx = h->pidx;
+    a.part = h->part;
+    a.nblocks = h->nblocks;
     a.dump = dump;
     if (h->variant < 0) return lm_head_f32(a, s);
-    return lm_head_tile_bf16(a, s);
+    if (h->variant == AJ_KERNEL_TILE) return lm_head_tile_bf16(a, s);
+    return lm_head_mfma_bf16(h->variant, a, h->num_cus, s);
 }
 
 extern "C" int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_d, const void *W_lm,
@@ -175,8 +194,7 @@ extern "C" int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_
     t.hidden_d = hidden_d;
     t.clf_w = clf_w;
     t.draft_tok = draft_tok;
-    t.pval = h->pval;
-    t.pidx = h->pidx;
+    t.part = h->part;
     t.nblocks = h->nblocks;
     t.B = c.B;
     t.K = c.K;
@@ -193,8 +211,7 @@ extern "C" int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_
     t.score = h->score;
     t.out_len = out_len;
     t.out_tok = out_tok;
-    if ((e = argmax_reduce(t, s)) != hipSuccess) return hip_fail(e);
-    if ((e = judge_scan(t, s)) != hipSuccess) return hip_fail(e);
+    if ((e = verify_tail(t, s)) != hipSuccess) return hip_fail(e);
     return AJ_OK;
 }
 

@@ -10,21 +10,21 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
+// (value, index) pair ordered by larger value, then lower index.
+struct __attribute__((aligned(8))) Best {
+    float v;
+    int32_t i;
+};
+
 // One LM-head launch: logits of M verify rows against V vocabulary rows, reduced per
 // (row, vocabulary block) to the block's maximum and its lowest index.
 struct LmHeadArgs {
     const void *H;      // [M][d] hidden_t
     const void *W;      // [V][d] W_lm
     int M, V, d;
-    float *pval;        // [nblocks][M] block maximum
-    int32_t *pidx;      // [nblocks][M] lowest vocabulary index attaining it
+    Best *part;         // [M][nblocks] block maximum and the lowest vocabulary index attaining it
+    int nblocks;        // partials per verify row (fixed by the kernel variant and V)
     float *dump;        // debug: all logits [M][V], or nullptr
-};
-
-// (value, index) pair ordered by larger value, then lower index.
-struct Best {
-    float v;
-    int32_t i;
 };
 
 __device__ __forceinline__ bool better(float v, int32_t i, float bv, int32_t bi)
@@ -35,16 +35,18 @@ __device__ __forceinline__ bool better(float v, int32_t i, float bv, int32_t bi)
 // Number of vocabulary blocks (partials per row) each variant produces for V.
 int lm_head_tile_blocks(int V);
 int lm_head_f32_blocks(int V);
+int lm_head_mfma_blocks(int variant, int V);               // variant: AJ_KERNEL_STREAM / AJ_KERNEL_BIG
+bool lm_head_mfma_supports(int variant, int M, int V, int d);
 
 // Launchers return hipSuccess or the launch error.
 hipError_t lm_head_tile_bf16(const LmHeadArgs &a, hipStream_t s);
 hipError_t lm_head_f32(const LmHeadArgs &a, hipStream_t s);
+hipError_t lm_head_mfma_bf16(int variant, const LmHeadArgs &a, int num_cus, hipStream_t s);
 
 struct TailArgs {
     const void *hidden_t, *hidden_d, *clf_w;
     const int32_t *draft_tok;
-    const float *pval;      // [nblocks][M]
-    const int32_t *pidx;
+    const Best *part;       // [M][nblocks]
     int nblocks;
     int B, K, d_t, d_d, V, dtype, feat_offset;
     float clf_b, zthr;      // zthr = log(tau/(1-tau)), -inf/+inf at the ends
@@ -53,7 +55,6 @@ struct TailArgs {
     float *score;           // [B][K] out or nullptr
     int32_t *out_len, *out_tok;
 };
-hipError_t argmax_reduce(const TailArgs &a, hipStream_t s);   // partials -> t_star, maxlogit
-hipError_t judge_scan(const TailArgs &a, hipStream_t s);      // steps 3-4
+hipError_t verify_tail(const TailArgs &a, hipStream_t s);     // partials -> t_star; steps 3-4
 
 }  // namespace aj

@@ -55,8 +55,7 @@ __global__ __launch_bounds__(256) void k_lm_head_f32(LmHeadArgs a)
             }
         }
         if (lane == 0 && row < a.M) {
-            a.pval[(size_t)blockIdx.y * a.M + row] = bv;
-            a.pidx[(size_t)blockIdx.y * a.M + row] = bi;
+            a.part[(size_t)row * a.nblocks + blockIdx.y] = Best{bv, bi};
         }
     }
 }

@@ -133,8 +133,7 @@ __global__ __launch_bounds__(256) void k_lm_head_tile(LmHeadArgs a)
                 bv = red_v[lr];
                 bi = red_i[lr];
             }
-            a.pval[(size_t)blockIdx.y * a.M + row] = bv;
-            a.pidx[(size_t)blockIdx.y * a.M + row] = bi;
+            a.part[(size_t)row * a.nblocks + blockIdx.y] = Best{bv, bi};
         }
         __syncthreads();
     }

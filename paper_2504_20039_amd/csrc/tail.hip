@@ -1,48 +1,14 @@
-// Steps 2 (second half) to 4: cross-block greedy maximum, mismatch test + judge, first-reject scan.
+// Steps 2 (second half) to 4 in one launch: cross-block greedy maximum, mismatch test + judge,
+// first-reject scan.  One workgroup per speculation window.
 #include "aj_internal.h"
 
 namespace aj {
 
 namespace {
 
-// ---------------------------------------------------------------- step 2: reduce the block partials
-// 64 verify rows per workgroup, 4 threads per row each scanning every 4th vocabulary block;
-// reads are coalesced over rows (partials are stored [block][row]).
-__global__ __launch_bounds__(256) void k_argmax_reduce(const float *pval, const int32_t *pidx, int nblocks,
-                                                       int M, int32_t *t_star, float *maxlogit)
-{
-    __shared__ float sv[4][64];
-    __shared__ int32_t si[4][64];
-    const int rl = threadIdx.x & 63, sl = threadIdx.x >> 6;
-    const int row = blockIdx.x * 64 + rl;
-    float bv = -INFINITY;
-    int32_t bi = 0x7fffffff;
-    if (row < M) {
-        for (int nb = sl; nb < nblocks; nb += 4) {
-            float v = pval[(size_t)nb * M + row];
-            int32_t i = pidx[(size_t)nb * M + row];
-            if (better(v, i, bv, bi)) {
-                bv = v;
-                bi = i;
-            }
-        }
-    }
-    sv[sl][rl] = bv;
-    si[sl][rl] = bi;
-    __syncthreads();
-    if (sl == 0 && row < M) {
-#pragma unroll
-        for (int s = 1; s < 4; ++s)
-            if (better(sv[s][rl], si[s][rl], bv, bi)) {
-                bv = sv[s][rl];
-                bi = si[s][rl];
-            }
-        t_star[row] = bi;
-        maxlogit[row] = bv;
-    }
-}
+constexpr int TAIL_WAVES = 8;
+constexpr int MAXK = 1023;
 
-// ---------------------------------------------------------------- steps 3-4
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 
@@ -72,19 +38,51 @@ __device__ __forceinline__ float dot_part(const void *x, const void *w, int n, i
     return acc;
 }
 
-// One workgroup per window.  Each wave takes every 4th slot; at a mismatching slot (a
-// wave-uniform condition) its 64 lanes share the judge dot product and reduce it with
-// cross-lane shuffles.  Wave 0 then finds the first rejected slot with ballots.
+// Phase 1: a wave per verify row reduces the row's block partials (coalesced: they are stored
+//          [row][block]) with lowest-index tie-break.
+// Phase 2: a wave per slot; at a mismatching slot (wave-uniform) its lanes share the judge dot
+//          product and reduce it with cross-lane shuffles.
+// Phase 3: wave 0 finds the first rejected slot with ballots and emits.
 template <bool BF16>
-__global__ __launch_bounds__(256) void k_judge_scan(TailArgs a)
+__global__ __launch_bounds__(TAIL_WAVES * 64) void k_verify_tail(TailArgs a)
 {
-    __shared__ uint8_t rej[1024];
+    __shared__ int32_t s_t[MAXK + 1];
+    __shared__ uint8_t s_rej[MAXK + 1];
     const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int K = a.K, R = K + 1;
     const size_t es = BF16 ? 2 : 4;
-    const int32_t *t = a.t_star + (size_t)b * R;
-    for (int j = wave; j < K; j += 4) {
-        const bool mis = t[j] != a.draft_tok[(size_t)b * K + j];
+
+    for (int j = wave; j < R; j += TAIL_WAVES) {
+        const size_t row = (size_t)b * R + j;
+        const Best *p = a.part + row * a.nblocks;
+        float bv = -INFINITY;
+        int32_t bi = 0x7fffffff;
+        for (int nb = lane; nb < a.nblocks; nb += 64) {
+            Best x = p[nb];
+            if (better(x.v, x.i, bv, bi)) {
+                bv = x.v;
+                bi = x.i;
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            float ov = __shfl_xor(bv, off);
+            int32_t oi = __shfl_xor(bi, off);
+            if (better(ov, oi, bv, bi)) {
+                bv = ov;
+                bi = oi;
+            }
+        }
+        if (lane == 0) {
+            s_t[j] = bi;
+            a.t_star[row] = bi;
+            a.maxlogit[row] = bv;
+        }
+    }
+    __syncthreads();
+
+    for (int j = wave; j < K; j += TAIL_WAVES) {
+        const bool mis = s_t[j] != a.draft_tok[(size_t)b * K + j];
         float z = __builtin_nanf("");
         bool r = false;
         if (mis) {
@@ -99,19 +97,20 @@ __global__ __launch_bounds__(256) void k_judge_scan(TailArgs a)
             r = !(z < a.zthr);
         }
         if (lane == 0) {
-            rej[j] = r;
+            s_rej[j] = r;
             if (a.score) {
                 a.score[(size_t)b * K + j] = z;
-                a.score[(size_t)a.B * K + (size_t)b * K + j] = 1.f / (1.f + __expf(-z));
+                a.score[(size_t)a.B * K + (size_t)b * K + j] = 1.f / (1.f + expf(-z));
             }
         }
     }
     __syncthreads();
+
     if (wave == 0) {
         int n = K;
         for (int base = 0; base < K; base += 64) {
             const int j = base + lane;
-            const bool r = j < K && rej[j];
+            const bool r = j < K && s_rej[j];
             const unsigned long long m = __ballot(r);
             if (m) {
                 n = base + __builtin_ctzll(m);
@@ -120,29 +119,20 @@ __global__ __launch_bounds__(256) void k_judge_scan(TailArgs a)
         }
         if (lane == 0) {
             a.out_len[b] = n;
-            a.out_tok[b] = t[n];
+            a.out_tok[b] = s_t[n];
         }
     }
 }
 
 }  // namespace
 
-hipError_t argmax_reduce(const TailArgs &a, hipStream_t s)
-{
-    const int M = a.B * (a.K + 1);
-    if (M <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_argmax_reduce, dim3((M + 63) / 64), dim3(256), 0, s, a.pval, a.pidx, a.nblocks, M,
-                       a.t_star, a.maxlogit);
-    return hipGetLastError();
-}
-
-hipError_t judge_scan(const TailArgs &a, hipStream_t s)
+hipError_t verify_tail(const TailArgs &a, hipStream_t s)
 {
     if (a.B <= 0) return hipSuccess;
     if (a.dtype == 1)
-        hipLaunchKernelGGL(k_judge_scan<true>, dim3(a.B), dim3(256), 0, s, a);
+        hipLaunchKernelGGL(k_verify_tail<true>, dim3(a.B), dim3(TAIL_WAVES * 64), 0, s, a);
     else
-        hipLaunchKernelGGL(k_judge_scan<false>, dim3(a.B), dim3(256), 0, s, a);
+        hipLaunchKernelGGL(k_verify_tail<false>, dim3(a.B), dim3(TAIL_WAVES * 64), 0, s, a);
     return hipGetLastError();
 }
 

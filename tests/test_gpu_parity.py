@@ -12,6 +12,16 @@ TINY = wl.WORKLOADS["tiny_f32"]
 KERNELS_BF16 = [1, 2, 3]          # AJ_KERNEL_TILE, _STREAM, _BIG (forced); 0 = AUTO is covered too
 
 
+def _skip_unless_supported(w, kernel):
+    """A forced LM-head variant refuses shapes it cannot run (AJ_EINVAL at aj_create)."""
+    import paper_2504_20039_amd as aj
+    try:
+        aj.aj_destroy(aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, w.dtype_code, 1, 0, kernel))
+    except aj.AjError as e:
+        assert e.status == -1
+        pytest.skip(f"kernel variant {kernel} does not take this shape")
+
+
 def test_tiny_f32_workload_with_all_logits():
     import torch
     import paper_2504_20039_amd as aj
@@ -37,11 +47,15 @@ def test_tiny_f32_workload_with_all_logits():
     dict(B=3, K=16, d_t=1024, d_d=512, V=2500),
     dict(B=2, K=1, d_t=64, d_d=8, V=130),
     dict(B=9, K=31, d_t=2048, d_d=256, V=777),         # M=288 spans several row tiles
+    dict(B=1, K=16, d_t=1024, d_d=256, V=5000),        # one skinny row block, several vocabulary tiles per CU
+    dict(B=2, K=15, d_t=384, d_d=128, V=70000),        # M=32 exactly; more tiles than workgroups
+    dict(B=20, K=31, d_t=512, d_d=64, V=3000),         # M=640: 3 row tiles x 12 column tiles of the large kernel
 ])
 def test_bf16_shapes_all_kernels(kernel, shape):
     import torch
     import paper_2504_20039_amd as aj
     w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="shape", p_match=0.6, **shape)
+    _skip_unless_supported(w, kernel)
     rep, x, draft, greedy, gpu = parity_case(w, 3, kernel=kernel, repeat=2)
     # all logits through the same kernel
     h = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, aj.AJ_BF16, 1, 0, kernel)
@@ -80,8 +94,8 @@ def test_monotone_in_tau_on_gpu():
         prev = gpu["out_len"]
 
 
-def _edge_inputs(seed=4, **kw):
-    w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="edge", B=4, K=12, d_t=256, d_d=64, V=1500, **kw)
+def _edge_inputs(seed=4, B=4, **kw):
+    w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="edge", B=B, K=12, d_t=256, d_d=64, V=1500, **kw)
     x = make_inputs(w, seed)
     return w, x, oracle_greedy(x)
 
@@ -108,7 +122,8 @@ def test_edge_draft_patterns():
 
 @pytest.mark.parametrize("kernel", [0] + KERNELS_BF16)
 def test_argmax_at_vocabulary_ends_and_exact_ties(kernel):
-    w, x, greedy = _edge_inputs(seed=6)
+    w, x, greedy = _edge_inputs(seed=6, B=2)        # 26 verify rows: every variant takes it
+    _skip_unless_supported(w, kernel)
     R = w.K + 1
     # make row 0's hidden state a big multiple of a chosen W_lm row's sign pattern: that row wins
     Wd = wl.widen(x.W)
