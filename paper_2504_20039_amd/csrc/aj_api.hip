@@ -107,7 +107,7 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
             return AJ_EINVAL;   // a forced variant that cannot run this shape
         }
         h->variant = v;
-        h->nblocks = v == AJ_KERNEL_TILE ? lm_head_tile_blocks(c.V) : lm_head_mfma_blocks(v, c.V);
+        h->nblocks = v == AJ_KERNEL_TILE ? lm_head_tile_blocks(c.V) : lm_head_mfma_blocks(v, c.V, c.d_t, h->num_cus);
     }
     if (h->M > 0) {
         const size_t np = (size_t)h->nblocks * h->M;

@@ -35,7 +35,7 @@ __device__ __forceinline__ bool better(float v, int32_t i, float bv, int32_t bi)
 // Number of vocabulary blocks (partials per row) each variant produces for V.
 int lm_head_tile_blocks(int V);
 int lm_head_f32_blocks(int V);
-int lm_head_mfma_blocks(int variant, int V);               // variant: AJ_KERNEL_STREAM / AJ_KERNEL_BIG
+int lm_head_mfma_blocks(int variant, int V, int d, int num_cus);  // variant: AJ_KERNEL_STREAM / AJ_KERNEL_BIG
 bool lm_head_mfma_supports(int variant, int M, int V, int d);
 
 // Launchers return hipSuccess or the launch error.

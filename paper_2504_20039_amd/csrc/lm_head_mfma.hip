@@ -16,7 +16,11 @@
 //     behind one L2 work on a compact block of tiles that share operand panels.
 //
 // Two instantiations:
-//   STREAM  128 vocabulary x 32 verify rows, BK = 128, 3 stages: W_lm-streaming (HBM-bound) regime
+//   STREAM  32 vocabulary x 32 verify rows per tile, BK = 256, 4 stages, the 4 waves split each
+//           stage's k range (partial sums are added through LDS once per tile).  Few rows with long
+//           contiguous segments in flight is what HBM wants: 2 KB of each W_lm row are in flight
+//           at a time.  Every workgroup keeps a running maximum over all its tiles and writes ONE
+//           partial per verify row.  W_lm-streaming (HBM-bound) regime, M <= 32.
 //   BIG     256 x 256, BK = 64, 2 stages: MFMA-bound regime
 #include "../../include/aj.h"
 #include "aj_internal.h"
@@ -28,6 +32,26 @@ namespace {
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void gbl_void;
 
+// Asynchronous 16-byte-per-lane load global -> LDS: lane i's data lands at lds_base + 16*i.
+// Written as inline assembly on purpose: with the compiler builtin, the compiler orders every later
+// LDS read after ALL outstanding loads of this kind (s_waitcnt vmcnt(0)), which would drain the
+// pipeline at every stage.  Here the kernel does its own accounting (wait_vm_and_barrier below); the
+// compiler sees only a memory clobber.  lds_dst must be wave-uniform (it travels in M0).
+__device__ __forceinline__ void load_to_lds_16(const char *base, uint32_t lane_off, uint32_t lds_dst)
+{
+    // base: wave-uniform global pointer; lane_off: this lane's unsigned byte offset from it
+    uint32_t saved_m0;   // M0 is reserved for the compiler: keep its value across the statement
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0)
+                 : "v"(lane_off), "s"(base), "s"(lds_dst)
+                 : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_offset_of(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char *)p;
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vm_and_barrier()
 {
@@ -37,28 +61,40 @@ __device__ __forceinline__ void wait_vm_and_barrier()
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-template <int TN_, int TM_, int WN_, int WM_, int BK_, int NS_>
+template <int TN_, int TM_, int WN_, int WM_, int WK_, int BK_, int NS_, bool RUNNING_, int HREG_KS_ = 0>
 struct Shape {
-    static constexpr int TN = TN_, TM = TM_, WN = WN_, WM = WM_, BK = BK_, NS = NS_;
-    static constexpr int NW = WN * WM;            // waves per workgroup
+    static constexpr int TN = TN_, TM = TM_, WN = WN_, WM = WM_, WK = WK_, BK = BK_, NS = NS_;
+    static constexpr bool RUNNING = RUNNING_;     // one running partial per workgroup (needs a single row tile)
+    // HREG_KS > 0: the hidden_t operand lives in REGISTERS for the whole kernel (each k-split wave keeps
+    // the fragments of its own k sub-range of every stage), d_t is fixed at HREG_KS * BK, the k loop is
+    // unrolled, and LDS stages hold W_lm only.
+    static constexpr int HREG_KS = HREG_KS_;
+    static constexpr bool HREG = HREG_KS_ > 0;
+    static constexpr int NW = WN * WM * WK;       // waves per workgroup
     static constexpr int BN = 32 * TN * WN;       // vocabulary rows per tile
     static constexpr int BM = 32 * TM * WM;       // verify rows per tile
     static constexpr int CH = BK / 8;             // 16-byte chunks per tile row
     static constexpr int RPI = 64 / CH;           // tile rows covered by one wave-wide load
     static constexpr int RPW = CH >= 16 ? 1 : 16 / CH;   // tile rows per 256-byte bank wrap
-    static constexpr int WI = BN / RPI, HI = BM / RPI;   // wave-wide loads per stage: W tile, H tile
+    static constexpr int SWM = CH >= 16 ? 16 : CH;       // swizzle modulus: XOR acts on the low bits of the chunk index
+    static constexpr int KSTEPS = BK / 16 / WK;   // k16 steps per wave per stage
+    static constexpr int WI = BN / RPI, HI = HREG ? 0 : BM / RPI;   // wave-wide loads per stage: W tile, H tile
     static constexpr int LPW = (WI + HI) / NW;    // loads per wave per stage
-    static constexpr int W_BYTES = BN * BK * 2, H_BYTES = BM * BK * 2;
+    static constexpr int W_BYTES = BN * BK * 2, H_BYTES = HREG ? 0 : BM * BK * 2;
     static constexpr int STAGE_BYTES = W_BYTES + H_BYTES;
-    static_assert(CH == 4 || CH == 8 || CH == 16, "BK must be 32, 64 or 128");
+    static constexpr int RED_BYTES = (WK - 1) * WN * WM * TN * TM * 16 * 64 * 4;   // k-split partial sums
+    static_assert(CH == 4 || CH == 8 || CH == 16 || CH == 32, "BK must be 32, 64, 128 or 256");
     static_assert(WI % NW == 0 && HI % NW == 0, "loads must split evenly over the waves");
-    static_assert((NW * RPI) % 16 == 0, "per-lane swizzle must not depend on the load index");
+    static_assert((BK / 16) % WK == 0, "k steps must split evenly over the k-split waves");
+    static_assert((NW * RPI) % 16 == 0, "the chunk a lane fetches must not depend on the load index");
     static_assert((NS - 2) * LPW <= 63, "vmcnt range");
-    static_assert(NS * STAGE_BYTES + BM * WN * 8 <= 160 * 1024, "LDS budget");
+    static_assert(NS * STAGE_BYTES + BM * WN * 8 + RED_BYTES <= 160 * 1024, "LDS budget");
+    static_assert(!HREG || (TM == 1 && WM == 1 && RUNNING), "register-resident hidden_t: one 32-row block");
 };
 
-using StreamShape = Shape<1, 1, 4, 1, 128, 3>;
-using BigShape = Shape<4, 4, 2, 2, 64, 2>;
+using StreamShape = Shape<1, 1, 4, 1, 1, 128, 3, true>;            // any d_t % 128 == 0
+using Stream4096Shape = Shape<1, 1, 1, 1, 8, 256, 8, true, 16>;     // d_t == 4096, hidden_t in registers
+using BigShape = Shape<4, 4, 2, 2, 1, 64, 2, false>;
 
 struct Sched {
     int tiles_m, tiles_n, gm, total;
@@ -79,15 +115,17 @@ __device__ __forceinline__ void tile_of(const Sched &sc, int T, int &mt, int &nt
 template <class S, bool DUMP>
 __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched sc)
 {
-    constexpr int TN = S::TN, TM = S::TM, WN = S::WN, NW = S::NW, BK = S::BK, NS = S::NS;
-    constexpr int CH = S::CH, RPI = S::RPI, RPW = S::RPW, LPW = S::LPW;
+    constexpr int TN = S::TN, TM = S::TM, WN = S::WN, WM = S::WM, WK = S::WK, NW = S::NW, BK = S::BK, NS = S::NS;
+    constexpr int CH = S::CH, RPI = S::RPI, RPW = S::RPW, SWM = S::SWM, LPW = S::LPW;
+    constexpr int AHEAD = NS - 1;                  // stages in flight ahead of the one being computed
     __shared__ __attribute__((aligned(1024))) char lds[NS * S::STAGE_BYTES];
     __shared__ Best red[S::BM * (WN > 1 ? WN - 1 : 1)];
+    __shared__ float redk[WK > 1 ? S::RED_BYTES / 4 : 1];
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wn = wave % WN, wm = wave / WN;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wn = wave % WN, wm = (wave / WN) % WM, wk = wave / (WN * WM);
     const int l32 = lane & 31, kh = lane >> 5;
-    const int d = a.d, KS = d / BK;
+    const int d = a.d, KS = S::HREG ? S::HREG_KS : d / BK;       // host guarantees KS >= AHEAD
     const char *W = (const char *)a.W, *H = (const char *)a.H;
 
     // ---- persistent tile list of this workgroup: runs of (gridDim/8) consecutive tiles per XCD
@@ -95,55 +133,107 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
     auto tile_at = [&](int step) { return (step * 8 + xcd) * SL + slot; };
 
     // ---- loader constants
-    const int rl = lane / CH;                                     // row inside one wave-wide load
-    const int cg = (lane % CH) ^ (((wave * RPI + rl) / RPW) % CH);  // global chunk landing at this lane's LDS slot
+    // A wave-wide load covers 1 KB of LDS = RPI whole tile rows; lane i fills slot (row i / CH,
+    // chunk i % CH) and must therefore fetch global chunk (i % CH) ^ swizzle(row).  Load j of wave w
+    // covers tile rows (j*NW + w)*RPI ..; NW*RPI is a multiple of the swizzle period (16 rows), so
+    // the chunk a lane fetches does not depend on j.
+    const int rl = lane / CH;
+    const uint32_t cg16 = (uint32_t)(((lane % CH) ^ (((wave * RPI + rl) / RPW) % SWM)) * 16);
+    const uint32_t rowbytes = (uint32_t)d * 2u;
+    const uint32_t lds_base = lds_offset_of(lds);
     // ---- fragment-read constants
-    const int swz = (l32 / RPW) % CH;
+    const int swz = (l32 / RPW) % SWM;
     const int a_row = (wn * TN * 32 + l32) * BK * 2;              // byte offset of the lane's row in the W tile
     const int b_row = S::W_BYTES + (wm * TM * 32 + l32) * BK * 2; // ... in the H tile
 
-    // issue cursor (tile, k-stage) runs NS-1 stages ahead of the compute cursor
-    int i_step = 0, i_ks = 0, i_buf = 0;
-    int i_T = tile_at(0), i_mt = 0, i_nt = 0;
-    if (i_T < sc.total) tile_of(sc, i_T, i_mt, i_nt);
-
-    auto issue = [&]() {
-        // one pipeline stage: the W tile [BN][BK] and the H tile [BM][BK] of (i_mt, i_nt) at k = i_ks*BK
-        const int n0 = i_nt * S::BN, m0 = i_mt * S::BM, kbyte = i_ks * BK * 2 + cg * 16;
-        char *stage = lds + i_buf * S::STAGE_BYTES;
+    // One pipeline stage: the W tile [BN][BK] and the H tile [BM][BK] of tile (mt, nt) at k = ks*BK, into
+    // ring buffer `buf`.  Each load is "uniform 64-bit base + 32-bit lane offset"; the lane offsets are
+    // recomputed at every stage (a few VALU ops beside hundreds of MFMA cycles) rather than kept in
+    // registers across the k loop - the laundered `rl_now` stops the compiler from hoisting them.
+    auto issue = [&](int mt, int nt, int ks, int buf) {
+        int rl_now = rl;
+        asm volatile("" : "+v"(rl_now));
+        const int n_first = nt * S::BN + wave * RPI + rl_now;     // the lane's row in load j = 0
+        const int m_first = mt * S::BM + wave * RPI + rl_now;
+        const uint32_t koff = (uint32_t)(ks * BK * 2) + cg16;
+        const uint32_t stage = lds_base + buf * S::STAGE_BYTES + wave * 1024;
 #pragma unroll
         for (int j = 0; j < LPW; ++j) {
-            const int q = j * NW + wave;                          // load index inside the stage (wave-uniform)
             if (j < S::WI / NW) {
-                const int row = min(n0 + q * RPI + rl, a.V - 1);  // clamped: ragged tiles stay in bounds
-                const char *g = W + (size_t)row * (size_t)(d * 2) + kbyte;
-                __builtin_amdgcn_global_load_lds((gbl_void *)g, (lds_void *)(stage + q * 1024), 16, 0, 0);
+                const int row = min(n_first + j * NW * RPI, a.V - 1);       // clamped: ragged tiles stay in bounds
+                load_to_lds_16(W, __umul24(row, rowbytes) + koff, stage + j * NW * 1024);
             } else {
-                const int qh = q - S::WI;
-                const int row = min(m0 + qh * RPI + rl, a.M - 1);
-                const char *g = H + (size_t)row * (size_t)(d * 2) + kbyte;
-                __builtin_amdgcn_global_load_lds((gbl_void *)g, (lds_void *)(stage + S::W_BYTES + qh * 1024), 16, 0, 0);
+                const int jj = j - S::WI / NW;
+                const int row = min(m_first + jj * NW * RPI, a.M - 1);
+                load_to_lds_16(H, __umul24(row, rowbytes) + koff, stage + S::W_BYTES + jj * NW * 1024);
             }
-        }
-        i_buf = (i_buf + 1 == NS) ? 0 : i_buf + 1;
-        if (++i_ks == KS) {
-            i_ks = 0;
-            i_T = tile_at(++i_step);
-            if (i_T < sc.total) tile_of(sc, i_T, i_mt, i_nt);
         }
     };
 
+    // register-resident hidden_t fragments (B operand): column = verify row (clamped), this wave's k steps
+    bf16x8 hf[S::HREG ? S::HREG_KS : 1][S::HREG ? S::KSTEPS : 1];
+    if (S::HREG) {
+        const char *hrow = H + (size_t)min(l32, a.M - 1) * (size_t)(d * 2);
 #pragma unroll
-    for (int p = 0; p < NS - 1; ++p)
-        if (i_T < sc.total) issue();
+        for (int ks = 0; ks < (S::HREG ? S::HREG_KS : 1); ++ks)
+#pragma unroll
+            for (int s0 = 0; s0 < S::KSTEPS; ++s0)
+                hf[ks][s0] = *(const bf16x8 *)(hrow + (ks * BK + (wk * S::KSTEPS + s0) * 16 + kh * 8) * 2);
+        // These ordinary loads must be complete, and known to the compiler to be complete, before the
+        // first asynchronous load is issued: otherwise the waits the compiler places before their
+        // first use inside the pipelined loop would drain the kernel's own in-flight loads.  Touching
+        // every register in an (empty) asm statement makes the compiler wait here.
+#pragma unroll
+        for (int ks = 0; ks < (S::HREG ? S::HREG_KS : 1); ++ks)
+#pragma unroll
+            for (int s0 = 0; s0 < S::KSTEPS; ++s0) asm volatile("" : "+v"(hf[ks][s0]));
+    }
 
     f32x16 acc[TN][TM];
-    int c_buf = 0;
-    for (int step = 0;; ++step) {
-        const int T = tile_at(step);
-        if (T >= sc.total) break;
-        int mt, nt;
+    float run_v[TM];
+    int32_t run_i[TM];
+#pragma unroll
+    for (int y = 0; y < TM; ++y) {
+        run_v[y] = -INFINITY;
+        run_i[y] = 0x7fffffff;
+    }
+
+    // MFMAs of one landed stage (ring buffer `buf`); this wave's share of the k steps
+    auto compute = [&](int ks, int buf) {
+        const char *stage = lds + buf * S::STAGE_BYTES;
+#pragma unroll
+        for (int s0 = 0; s0 < S::KSTEPS; ++s0) {
+            const int s = wk * S::KSTEPS + s0;
+            const int pos = ((2 * s + kh) ^ swz) * 16;
+            bf16x8 fa[TN], fb[TM];
+#pragma unroll
+            for (int x = 0; x < TN; ++x) fa[x] = *(const bf16x8 *)(stage + a_row + x * 32 * BK * 2 + pos);
+#pragma unroll
+            for (int y = 0; y < TM; ++y) {
+                if (S::HREG) fb[y] = hf[S::HREG ? ks : 0][s0];
+                else fb[y] = *(const bf16x8 *)(stage + b_row + y * 32 * BK * 2 + pos);
+            }
+#pragma unroll
+            for (int x = 0; x < TN; ++x)
+#pragma unroll
+                for (int y = 0; y < TM; ++y)
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[x], fb[y], acc[x][y], 0, 0, 0);
+        }
+    };
+
+    int T = tile_at(0);
+    int mt = 0, nt = 0, buf = 0;       // buf: ring buffer of the stage computed next
+    if (T < sc.total) {
         tile_of(sc, T, mt, nt);
+#pragma unroll
+        for (int p = 0; p < AHEAD; ++p) issue(mt, nt, p, p);
+    }
+
+    for (int step = 0; T < sc.total; ++step) {
+        const int T2 = tile_at(step + 1);
+        const bool have_next = T2 < sc.total;
+        int mt2 = 0, nt2 = 0;
+        if (have_next) tile_of(sc, T2, mt2, nt2);
 #pragma unroll
         for (int x = 0; x < TN; ++x)
 #pragma unroll
@@ -151,34 +241,67 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
-        for (int ks = 0; ks < KS; ++ks) {
-            // stage (T, ks) has landed once at most the NS-2 younger stages are outstanding;
-            // when the issue cursor is exhausted fewer are in flight, so wait for everything.
-            if (i_T < sc.total) {
+        // Stage ks has landed once at most the NS-2 younger stages are outstanding (loads complete in
+        // order).  The barrier also frees the buffer computed in the previous iteration, which is the
+        // one the new loads go to.  Hot part: the stage issued belongs to the same tile - no branches.
+        if (S::HREG) {
+#pragma unroll
+            for (int ks = 0; ks < (S::HREG ? S::HREG_KS - AHEAD : 0); ++ks) {
                 wait_vm_and_barrier<(NS - 2) * LPW>();
-                issue();                                  // into the buffer freed by the barrier
+                issue(mt, nt, ks + AHEAD, (buf + AHEAD) % NS);
+                compute(ks, buf);
+                buf = (buf + 1) % NS;
+            }
+        } else {
+            for (int ks = 0; ks < KS - AHEAD; ++ks) {
+                wait_vm_and_barrier<(NS - 2) * LPW>();
+                issue(mt, nt, ks + AHEAD, buf + AHEAD >= NS ? buf + AHEAD - NS : buf + AHEAD);
+                compute(ks, buf);
+                buf = buf + 1 == NS ? 0 : buf + 1;
+            }
+        }
+        // Last AHEAD stages of the tile: prefetch the first stages of the next tile, if there is one;
+        // otherwise fewer loads are in flight than the constant assumes, so wait for all of them.
+#pragma unroll
+        for (int p = 0; p < AHEAD; ++p) {
+            if (have_next) {
+                wait_vm_and_barrier<(NS - 2) * LPW>();
+                issue(mt2, nt2, p, buf + AHEAD >= NS ? buf + AHEAD - NS : buf + AHEAD);
             } else {
                 wait_vm_and_barrier<0>();
             }
-            const char *stage = lds + c_buf * S::STAGE_BYTES;
-#pragma unroll
-            for (int s = 0; s < BK / 16; ++s) {
-                const int pos = ((2 * s + kh) ^ swz) * 16;
-                bf16x8 fa[TN], fb[TM];
-#pragma unroll
-                for (int x = 0; x < TN; ++x) fa[x] = *(const bf16x8 *)(stage + a_row + x * 32 * BK * 2 + pos);
-#pragma unroll
-                for (int y = 0; y < TM; ++y) fb[y] = *(const bf16x8 *)(stage + b_row + y * 32 * BK * 2 + pos);
+            compute(S::HREG ? S::HREG_KS - AHEAD + p : KS - AHEAD + p, buf);
+            buf = buf + 1 == NS ? 0 : buf + 1;
+        }
+
+        // ---- k-split waves: add the partial sums of waves wk > 0 into wave wk == 0 (through LDS)
+        if (WK > 1) {
+            const int blk = (wm * WN + wn) * TN * TM;
+            if (wk > 0) {
 #pragma unroll
                 for (int x = 0; x < TN; ++x)
 #pragma unroll
                     for (int y = 0; y < TM; ++y)
-                        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[x], fb[y], acc[x][y], 0, 0, 0);
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            redk[((((wk - 1) * WN * WM * TN * TM + blk + x * TM + y) * 16) + r) * 64 + lane] = acc[x][y][r];
             }
-            c_buf = (c_buf + 1 == NS) ? 0 : c_buf + 1;
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            if (wk == 0) {
+#pragma unroll
+                for (int w = 1; w < WK; ++w)
+#pragma unroll
+                    for (int x = 0; x < TN; ++x)
+#pragma unroll
+                        for (int y = 0; y < TM; ++y)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r)
+                                acc[x][y][r] += redk[((((w - 1) * WN * WM * TN * TM + blk + x * TM + y) * 16) + r) * 64 + lane];
+            }
+            // redk is rewritten only after the k-loop barriers of the next tile
         }
 
-        // ---- epilogue: D register r of a lane = vocabulary row 8*(r/4) + 4*(lane/32) + r%4 of its block
+        // ---- greedy maximum: D register r of a lane = vocabulary row 8*(r/4) + 4*(lane/32) + r%4 of its block
         const int v_base = nt * S::BN + wn * TN * 32 + kh * 4;
         float pv[TM];
         int32_t pi[TM];
@@ -186,8 +309,8 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
         for (int y = 0; y < TM; ++y) {
             const int lr = wm * TM * 32 + y * 32 + l32;          // verify row inside the tile
             const int row = mt * S::BM + lr;
-            float bv = -INFINITY;
-            int32_t bi = 0x7fffffff;
+            float bv = S::RUNNING ? run_v[y] : -INFINITY;
+            int32_t bi = S::RUNNING ? run_i[y] : 0x7fffffff;
 #pragma unroll
             for (int x = 0; x < TN; ++x)
 #pragma unroll
@@ -195,13 +318,19 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                     const int v = v_base + x * 32 + (r >> 2) * 8 + (r & 3);
                     const float val = acc[x][y][r];
                     if (v < a.V) {
-                        if (DUMP && row < a.M) a.dump[(size_t)row * a.V + v] = val;
+                        if (DUMP && row < a.M && wk == 0) a.dump[(size_t)row * a.V + v] = val;
+                        // ascending v inside a lane and over a workgroup's tiles: strict > keeps the lowest
                         if (val > bv) {
                             bv = val;
                             bi = v;
                         }
                     }
                 }
+            if (S::RUNNING) {
+                run_v[y] = bv;
+                run_i[y] = bi;
+                continue;
+            }
             const float ov = __shfl_xor(bv, 32);
             const int32_t oi = __shfl_xor(bi, 32);
             if (better(ov, oi, bv, bi)) {
@@ -212,28 +341,61 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
             pv[y] = bv;
             pi[y] = bi;
         }
-        // LDS writes of `red` done and visible; do not wait for the prefetch loads in flight
-        if (WN > 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        if (wn == 0 && kh == 0) {
+        if (!S::RUNNING) {
+            // LDS writes of `red` done and visible; do not wait for the prefetch loads in flight
+            if (WN > 1) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            if (wn == 0 && kh == 0 && wk == 0) {
 #pragma unroll
-            for (int y = 0; y < TM; ++y) {
-                const int lr = wm * TM * 32 + y * 32 + l32;
-                const int row = mt * S::BM + lr;
-                float bv = pv[y];
-                int32_t bi = pi[y];
+                for (int y = 0; y < TM; ++y) {
+                    const int lr = wm * TM * 32 + y * 32 + l32;
+                    const int row = mt * S::BM + lr;
+                    float bv = pv[y];
+                    int32_t bi = pi[y];
 #pragma unroll
-                for (int w = 1; w < WN; ++w) {
-                    const Best o = red[(w - 1) * S::BM + lr];
-                    if (better(o.v, o.i, bv, bi)) {
-                        bv = o.v;
-                        bi = o.i;
+                    for (int w = 1; w < WN; ++w) {
+                        const Best o = red[(w - 1) * S::BM + lr];
+                        if (better(o.v, o.i, bv, bi)) {
+                            bv = o.v;
+                            bi = o.i;
+                        }
                     }
+                    if (row < a.M) a.part[(size_t)row * a.nblocks + nt] = Best{bv, bi};
                 }
-                if (row < a.M) a.part[(size_t)row * a.nblocks + nt] = Best{bv, bi};
             }
+            // `red` is next written after the k-loop barriers of the following tile: no extra barrier
         }
-        // `red` is next written after the k-loop barriers of the following tile: no extra barrier
+        T = T2;
+        mt = mt2;
+        nt = nt2;
     }
+
+    if (S::RUNNING) {
+        // one partial per verify row, workgroup and wave column (a neutral one if there was no tile)
+        static_assert(!S::RUNNING || WM == 1, "running partials: a single row tile");
+#pragma unroll
+        for (int y = 0; y < TM; ++y) {
+            float bv = run_v[y];
+            int32_t bi = run_i[y];
+            const float ov = __shfl_xor(bv, 32);
+            const int32_t oi = __shfl_xor(bi, 32);
+            if (better(ov, oi, bv, bi)) {
+                bv = ov;
+                bi = oi;
+            }
+            const int row = y * 32 + l32;
+            if (wk == 0 && kh == 0 && row < a.M)
+                a.part[(size_t)row * a.nblocks + blockIdx.x * WN + wn] = Best{bv, bi};
+        }
+    }
+}
+
+int grid_for(int num_cus, int total_tiles)
+{
+    int grid = (num_cus / 8) * 8;
+    if (grid < 8) grid = 8;
+    // no more workgroups than tiles (rounded up to the XCD count so that the run mapping holds)
+    const int need = ((total_tiles + 7) / 8) * 8;
+    return grid > need ? need : grid;
 }
 
 template <class S>
@@ -244,11 +406,7 @@ hipError_t launch(const LmHeadArgs &a, int num_cus, int gm, hipStream_t s)
     sc.tiles_n = (a.V + S::BN - 1) / S::BN;
     sc.gm = gm < 1 ? 1 : (gm > sc.tiles_m ? sc.tiles_m : gm);
     sc.total = sc.tiles_m * sc.tiles_n;
-    int grid = (num_cus / 8) * 8;
-    if (grid < 8) grid = 8;
-    // no more workgroups than tiles (rounded up to the XCD count so that the run mapping holds)
-    const int need = ((sc.total + 7) / 8) * 8;
-    if (grid > need) grid = need;
+    const int grid = grid_for(num_cus, sc.total);
     if (a.dump)
         hipLaunchKernelGGL((k_lm_head_mfma<S, true>), dim3(grid), dim3(S::NW * 64), 0, s, a, sc);
     else
@@ -258,24 +416,36 @@ hipError_t launch(const LmHeadArgs &a, int num_cus, int gm, hipStream_t s)
 
 }  // namespace
 
-int lm_head_mfma_blocks(int variant, int V)
+static bool use_stream4096(int d) { return d == Stream4096Shape::HREG_KS * Stream4096Shape::BK; }
+
+int lm_head_mfma_blocks(int variant, int V, int d, int num_cus)
 {
-    const int bn = variant == AJ_KERNEL_STREAM ? StreamShape::BN : BigShape::BN;
-    return (V + bn - 1) / bn;
+    if (variant == AJ_KERNEL_STREAM) {  // one running partial per workgroup
+        if (use_stream4096(d))
+            return grid_for(num_cus, (V + Stream4096Shape::BN - 1) / Stream4096Shape::BN) * Stream4096Shape::WN;
+        return grid_for(num_cus, (V + StreamShape::BN - 1) / StreamShape::BN) * StreamShape::WN;
+    }
+    return (V + BigShape::BN - 1) / BigShape::BN;
 }
 
 bool lm_head_mfma_supports(int variant, int M, int V, int d)
 {
     if (M <= 0 || V <= 0) return false;
-    if (variant == AJ_KERNEL_STREAM) return d % StreamShape::BK == 0 && M <= StreamShape::BM;
-    if (variant == AJ_KERNEL_BIG) return d % BigShape::BK == 0;
+    // lane offsets are 32-bit and row indices go through a 24-bit multiply
+    if ((uint64_t)V * d * 2 >= (1ull << 32) || (uint64_t)M * d * 2 >= (1ull << 32)) return false;
+    if (V >= (1 << 24) || M >= (1 << 24) || d * 2 >= (1 << 24)) return false;
+    // whole k stages only, and at least as many as the pipeline runs ahead
+    if (variant == AJ_KERNEL_STREAM)
+        return d % StreamShape::BK == 0 && d / StreamShape::BK >= StreamShape::NS - 1 && M <= StreamShape::BM;
+    if (variant == AJ_KERNEL_BIG) return d % BigShape::BK == 0 && d / BigShape::BK >= BigShape::NS - 1;
     return false;
 }
 
 hipError_t lm_head_mfma_bf16(int variant, const LmHeadArgs &a, int num_cus, hipStream_t s)
 {
     if (a.M <= 0) return hipSuccess;
-    if (variant == AJ_KERNEL_STREAM) return launch<StreamShape>(a, num_cus, 1, s);
+    if (variant == AJ_KERNEL_STREAM)
+        return use_stream4096(a.d) ? launch<Stream4096Shape>(a, num_cus, 1, s) : launch<StreamShape>(a, num_cus, 1, s);
     return launch<BigShape>(a, num_cus, 8, s);
 }
 
