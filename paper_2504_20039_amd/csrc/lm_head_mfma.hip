@@ -61,7 +61,7 @@ __device__ __forceinline__ void wait_vm_and_barrier()
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-template <int TN_, int TM_, int WN_, int WM_, int WK_, int BK_, int NS_, bool RUNNING_, int HREG_KS_ = 0>
+template <int TN_, int TM_, int WN_, int WM_, int WK_, int BK_, int NS_, bool RUNNING_, int HREG_KS_ = 0, bool PIPE_ = false>
 struct Shape {
     static constexpr int TN = TN_, TM = TM_, WN = WN_, WM = WM_, WK = WK_, BK = BK_, NS = NS_;
     static constexpr bool RUNNING = RUNNING_;     // one running partial per workgroup (needs a single row tile)
@@ -70,6 +70,10 @@ struct Shape {
     // unrolled, and LDS stages hold W_lm only.
     static constexpr int HREG_KS = HREG_KS_;
     static constexpr bool HREG = HREG_KS_ > 0;
+    // PIPE: MFMA-bound schedule.  Fragments of k step s+1 are read while the MFMAs of step s run, the
+    // stage's loads are issued in KSTEPS parts between them, and the wait + barrier for the NEXT
+    // stage sits before the MFMAs of a stage's last k step, so the matrix pipe never waits for it.
+    static constexpr bool PIPE = PIPE_;
     static constexpr int NW = WN * WM * WK;       // waves per workgroup
     static constexpr int BN = 32 * TN * WN;       // vocabulary rows per tile
     static constexpr int BM = 32 * TM * WM;       // verify rows per tile
@@ -90,11 +94,16 @@ struct Shape {
     static_assert((NS - 2) * LPW <= 63, "vmcnt range");
     static_assert(NS * STAGE_BYTES + BM * WN * 8 + RED_BYTES <= 160 * 1024, "LDS budget");
     static_assert(!HREG || (TM == 1 && WM == 1 && RUNNING), "register-resident hidden_t: one 32-row block");
+    static constexpr int LPP = LPW / KSTEPS;      // PIPE: loads per wave per k step
+    static_assert(!PIPE || (!HREG && WK == 1 && NS >= 3 && KSTEPS % 2 == 0 && LPW % KSTEPS == 0 &&
+                            (WI / NW) % LPP == 0),
+                  "pipelined schedule: two fragment sets alternate, loads split evenly over the k steps");
+    static_assert(!PIPE || (NS - 3) * LPW + (KSTEPS - 1) * LPP <= 63, "vmcnt range");
 };
 
 using StreamShape = Shape<1, 1, 4, 1, 1, 128, 3, true>;            // any d_t % 128 == 0
 using Stream4096Shape = Shape<1, 1, 1, 1, 8, 256, 8, true, 16>;     // d_t == 4096, hidden_t in registers
-using BigShape = Shape<4, 4, 2, 2, 1, 64, 2, false>;
+using BigShape = Shape<4, 4, 2, 2, 1, 32, 4, false, 0, true>;
 
 struct Sched {
     int tiles_m, tiles_n, gm, total;
@@ -110,6 +119,14 @@ __device__ __forceinline__ void tile_of(const Sched &sc, int T, int &mt, int &nt
     const int g = (grp == ngroups - 1) ? sc.tiles_m - grp * sc.gm : sc.gm;
     mt = grp * sc.gm + within % g;
     nt = within / g;
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vm_lgkm_and_barrier()
+{
+    // as above, and this wave's LDS reads have returned (its buffer may be overwritten after the barrier)
+    static_assert(N >= 0 && N <= 63, "vmcnt field");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
 template <class S, bool DUMP>
@@ -150,7 +167,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
     // ring buffer `buf`.  Each load is "uniform 64-bit base + 32-bit lane offset"; the lane offsets are
     // recomputed at every stage (a few VALU ops beside hundreds of MFMA cycles) rather than kept in
     // registers across the k loop - the laundered `rl_now` stops the compiler from hoisting them.
-    auto issue = [&](int mt, int nt, int ks, int buf) {
+    auto issue = [&](int mt, int nt, int ks, int buf, int part = -1) {   // part >= 0: only that share of the loads
         int rl_now = rl;
         asm volatile("" : "+v"(rl_now));
         const int n_first = nt * S::BN + wave * RPI + rl_now;     // the lane's row in load j = 0
@@ -159,6 +176,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
         const uint32_t stage = lds_base + buf * S::STAGE_BYTES + wave * 1024;
 #pragma unroll
         for (int j = 0; j < LPW; ++j) {
+            if (part >= 0 && j / S::LPP != part) continue;
             if (j < S::WI / NW) {
                 const int row = min(n_first + j * NW * RPI, a.V - 1);       // clamped: ragged tiles stay in bounds
                 load_to_lds_16(W, __umul24(row, rowbytes) + koff, stage + j * NW * 1024);
@@ -221,12 +239,34 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
         }
     };
 
+    // PIPE: two fragment sets
+    bf16x8 fa[2][TN], fb[2][TM];
+    auto read_frags = [&](int buf, int s, bf16x8(&ra)[TN], bf16x8(&rb)[TM]) {
+        const char *stage = lds + buf * S::STAGE_BYTES;
+        const int pos = ((2 * s + kh) ^ swz) * 16;
+#pragma unroll
+        for (int x = 0; x < TN; ++x) ra[x] = *(const bf16x8 *)(stage + a_row + x * 32 * BK * 2 + pos);
+#pragma unroll
+        for (int y = 0; y < TM; ++y) rb[y] = *(const bf16x8 *)(stage + b_row + y * 32 * BK * 2 + pos);
+    };
+    auto mfmas = [&](const bf16x8(&ra)[TN], const bf16x8(&rb)[TM]) {
+#pragma unroll
+        for (int x = 0; x < TN; ++x)
+#pragma unroll
+            for (int y = 0; y < TM; ++y)
+                acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ra[x], rb[y], acc[x][y], 0, 0, 0);
+    };
+
     int T = tile_at(0);
     int mt = 0, nt = 0, buf = 0;       // buf: ring buffer of the stage computed next
     if (T < sc.total) {
         tile_of(sc, T, mt, nt);
 #pragma unroll
         for (int p = 0; p < AHEAD; ++p) issue(mt, nt, p, p);
+        if (S::PIPE) {
+            wait_vm_lgkm_and_barrier<(AHEAD - 1) * LPW>();
+            read_frags(0, 0, fa[0], fb[0]);
+        }
     }
 
     for (int step = 0; T < sc.total; ++step) {
@@ -241,6 +281,39 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
+        if (S::PIPE) {
+            // fragments of (stage ks, step 0) are already in set 0: read after the previous stage's early barrier
+            auto pipe_stage = [&](int ks, bool hot) {
+                const int nbuf = buf + 1 == NS ? 0 : buf + 1;                       // next stage's buffer
+                const int ibuf = buf + AHEAD >= NS ? buf + AHEAD - NS : buf + AHEAD; // buffer being refilled
+                const bool next_stage = hot || ks + 1 < KS || have_next;
+                const int iks = ks + AHEAD;                                         // stage being issued
+                const bool same_tile = hot || iks < KS;
+#pragma unroll
+                for (int s0 = 0; s0 < S::KSTEPS; ++s0) {
+                    const int cur = s0 & 1;
+                    if (s0 + 1 < S::KSTEPS) {
+                        read_frags(buf, s0 + 1, fa[cur ^ 1], fb[cur ^ 1]);
+                    } else if (next_stage) {
+                        // Stage ks+1 has landed once the loads issued after it are all that is outstanding:
+                        // AHEAD-2 whole stages and the first KSTEPS-1 parts of stage ks+AHEAD.  Without a
+                        // next tile fewer loads are in flight than that: wait for all.  All LDS reads of
+                        // stage ks were issued a k step ago (lgkmcnt(0) is cheap) - after the barrier its
+                        // buffer may be refilled.
+                        if (hot || have_next) wait_vm_lgkm_and_barrier<(NS - 3) * LPW + (S::KSTEPS - 1) * S::LPP>();
+                        else wait_vm_lgkm_and_barrier<0>();
+                        read_frags(nbuf, 0, fa[cur ^ 1], fb[cur ^ 1]);
+                    }
+                    if (same_tile) issue(mt, nt, iks, ibuf, s0);
+                    else if (have_next) issue(mt2, nt2, iks - KS, ibuf, s0);
+                    mfmas(fa[cur], fb[cur]);
+                }
+                buf = nbuf;
+            };
+            for (int ks = 0; ks < KS - AHEAD; ++ks) pipe_stage(ks, true);
+#pragma unroll
+            for (int p = 0; p < AHEAD; ++p) pipe_stage(KS - AHEAD + p, false);
+        } else {
         // Stage ks has landed once at most the NS-2 younger stages are outstanding (loads complete in
         // order).  The barrier also frees the buffer computed in the previous iteration, which is the
         // one the new loads go to.  Hot part: the stage issued belongs to the same tile - no branches.
@@ -272,6 +345,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
             }
             compute(S::HREG ? S::HREG_KS - AHEAD + p : KS - AHEAD + p, buf);
             buf = buf + 1 == NS ? 0 : buf + 1;
+        }
         }
 
         // ---- k-split waves: add the partial sums of waves wk > 0 into wave wk == 0 (through LDS)
