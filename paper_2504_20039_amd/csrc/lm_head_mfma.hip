@@ -24,6 +24,7 @@
 //   BIG     256 x 256, BK = 64, 2 stages: MFMA-bound regime
 #include "../../include/aj.h"
 #include "aj_internal.h"
+#include <stdlib.h>
 
 namespace aj {
 
@@ -45,6 +46,13 @@ __device__ __forceinline__ void load_to_lds_16(const char *base, uint32_t lane_o
                  : "=&s"(saved_m0)
                  : "v"(lane_off), "s"(base), "s"(lds_dst)
                  : "memory");
+}
+
+// Same load for the hand-scheduled loop: two instructions, M0 not restored (nothing else in these
+// kernels uses M0, and the compiler sets it itself before any use of its own).
+__device__ __forceinline__ void lds_dma_16(const char *base, uint32_t lane_off, uint32_t lds_dst)
+{
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(lds_dst) : "memory");
 }
 
 __device__ __forceinline__ uint32_t lds_offset_of(const void *p)
@@ -95,10 +103,10 @@ struct Shape {
     static_assert(NS * STAGE_BYTES + BM * WN * 8 + RED_BYTES <= 160 * 1024, "LDS budget");
     static_assert(!HREG || (TM == 1 && WM == 1 && RUNNING), "register-resident hidden_t: one 32-row block");
     static constexpr int LPP = LPW / KSTEPS;      // PIPE: loads per wave per k step
-    static_assert(!PIPE || (!HREG && WK == 1 && NS >= 3 && KSTEPS % 2 == 0 && LPW % KSTEPS == 0 &&
-                            (WI / NW) % LPP == 0),
-                  "pipelined schedule: two fragment sets alternate, loads split evenly over the k steps");
-    static_assert(!PIPE || (NS - 3) * LPW + (KSTEPS - 1) * LPP <= 63, "vmcnt range");
+    static_assert(!PIPE || (!HREG && WK == 1 && NS >= 3 && KSTEPS == 2 && TN == 4 && TM == 4 && WI / NW == 4 &&
+                            HI / NW == 4),
+                  "hand-scheduled stage: 4x4 blocks, 2 k steps, 4 + 4 loads per wave");
+    static_assert(!PIPE || (NS - 3) * LPW + 6 <= 63, "vmcnt range");
 };
 
 using StreamShape = Shape<1, 1, 4, 1, 1, 128, 3, true>;            // any d_t % 128 == 0
@@ -107,6 +115,7 @@ using BigShape = Shape<4, 4, 2, 2, 1, 32, 4, false, 0, true>;
 
 struct Sched {
     int tiles_m, tiles_n, gm, total;
+    int exp;   // TEMP
 };
 
 __device__ __forceinline__ void tile_of(const Sched &sc, int T, int &mt, int &nt)
@@ -177,6 +186,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
 #pragma unroll
         for (int j = 0; j < LPW; ++j) {
             if (part >= 0 && j / S::LPP != part) continue;
+            if (sc.exp & 1) continue;
             if (j < S::WI / NW) {
                 const int row = min(n_first + j * NW * RPI, a.V - 1);       // clamped: ragged tiles stay in bounds
                 load_to_lds_16(W, __umul24(row, rowbytes) + koff, stage + j * NW * 1024);
@@ -242,6 +252,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
     // PIPE: two fragment sets
     bf16x8 fa[2][TN], fb[2][TM];
     auto read_frags = [&](int buf, int s, bf16x8(&ra)[TN], bf16x8(&rb)[TM]) {
+        if (sc.exp & 2) return;
         const char *stage = lds + buf * S::STAGE_BYTES;
         const int pos = ((2 * s + kh) ^ swz) * 16;
 #pragma unroll
@@ -249,18 +260,22 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
 #pragma unroll
         for (int y = 0; y < TM; ++y) rb[y] = *(const bf16x8 *)(stage + b_row + y * 32 * BK * 2 + pos);
     };
-    auto mfmas = [&](const bf16x8(&ra)[TN], const bf16x8(&rb)[TM]) {
+    // PIPE: lane offsets of the 8 loads of a stage, fixed per tile (4 W_lm rows, 4 hidden_t rows)
+    uint32_t voff[8];
+    auto tile_offsets = [&](int mt_, int nt_, uint32_t(&vo)[8]) {
+        const int n_first = nt_ * S::BN + wave * RPI + rl, m_first = mt_ * S::BM + wave * RPI + rl;
 #pragma unroll
-        for (int x = 0; x < TN; ++x)
-#pragma unroll
-            for (int y = 0; y < TM; ++y)
-                acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ra[x], rb[y], acc[x][y], 0, 0, 0);
+        for (int j = 0; j < 4; ++j) {
+            vo[j] = __umul24(min(n_first + j * NW * RPI, a.V - 1), rowbytes) + cg16;
+            vo[4 + j] = __umul24(min(m_first + j * NW * RPI, a.M - 1), rowbytes) + cg16;
+        }
     };
 
     int T = tile_at(0);
     int mt = 0, nt = 0, buf = 0;       // buf: ring buffer of the stage computed next
     if (T < sc.total) {
         tile_of(sc, T, mt, nt);
+        if (S::PIPE) tile_offsets(mt, nt, voff);
 #pragma unroll
         for (int p = 0; p < AHEAD; ++p) issue(mt, nt, p, p);
         if (S::PIPE) {
@@ -282,37 +297,74 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                 for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
         if (S::PIPE) {
-            // fragments of (stage ks, step 0) are already in set 0: read after the previous stage's early barrier
+            // Hand-scheduled stage for the MFMA-bound shape (4x4 blocks per wave, 2 k steps, 8 loads
+            // per wave and stage).  With one wave per SIMD every instruction that is not an MFMA
+            // must sit in the shadow of a running MFMA, so the 16 MFMAs of a k step go out in 4
+            // groups of 4 (128 cycles each) and at most 4 LDS reads or 2 loads follow each group;
+            // sched_barrier pins that order.  Fragments of (stage ks, step 0) are already in set 0
+            // (read after the previous stage's early barrier).
+            //   step 0:  G0 r r r r | G1 r r r r | G2 L L | G3 L L          (reads: step 1 of this stage)
+            //   step 1:  G0 L L | G1 wait+barrier r r r r | G2 r r r r | G3 L L   (reads: step 0 of stage ks+1)
+            // At the barrier the loads younger than stage ks+1 are AHEAD-2 whole stages plus 6 of the
+            // stage being issued.  Without a next tile fewer loads are in flight: wait for all.
+            uint32_t voff2[8];
+            if (have_next) tile_offsets(mt2, nt2, voff2);
             auto pipe_stage = [&](int ks, bool hot) {
                 const int nbuf = buf + 1 == NS ? 0 : buf + 1;                       // next stage's buffer
                 const int ibuf = buf + AHEAD >= NS ? buf + AHEAD - NS : buf + AHEAD; // buffer being refilled
                 const bool next_stage = hot || ks + 1 < KS || have_next;
-                const int iks = ks + AHEAD;                                         // stage being issued
-                const bool same_tile = hot || iks < KS;
+                const bool same_tile = hot || ks + AHEAD < KS;
+                const bool issuing = same_tile || have_next;
+                const int iks = same_tile ? ks + AHEAD : ks + AHEAD - KS;           // stage being issued
+                const char *Wk = W + iks * BK * 2, *Hk = H + iks * BK * 2;
+                const uint32_t dst = lds_base + ibuf * S::STAGE_BYTES + wave * 1024;
+                auto L = [&](int j) {
+                    if (!issuing) return;
+                    const uint32_t vo = same_tile ? voff[j] : voff2[j];
+                    if (j < 4) lds_dma_16(Wk, vo, dst + j * NW * 1024);
+                    else lds_dma_16(Hk, vo, dst + S::W_BYTES + (j - 4) * NW * 1024);
+                };
+                auto Gx = [&](int cur, int x) {
 #pragma unroll
-                for (int s0 = 0; s0 < S::KSTEPS; ++s0) {
-                    const int cur = s0 & 1;
-                    if (s0 + 1 < S::KSTEPS) {
-                        read_frags(buf, s0 + 1, fa[cur ^ 1], fb[cur ^ 1]);
-                    } else if (next_stage) {
-                        // Stage ks+1 has landed once the loads issued after it are all that is outstanding:
-                        // AHEAD-2 whole stages and the first KSTEPS-1 parts of stage ks+AHEAD.  Without a
-                        // next tile fewer loads are in flight than that: wait for all.  All LDS reads of
-                        // stage ks were issued a k step ago (lgkmcnt(0) is cheap) - after the barrier its
-                        // buffer may be refilled.
-                        if (hot || have_next) wait_vm_lgkm_and_barrier<(NS - 3) * LPW + (S::KSTEPS - 1) * S::LPP>();
-                        else wait_vm_lgkm_and_barrier<0>();
-                        read_frags(nbuf, 0, fa[cur ^ 1], fb[cur ^ 1]);
+                    for (int y = 0; y < TM; ++y)
+                        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][x], fb[cur][y], acc[x][y], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                };
+                // fragment i of (buffer b, step s) into set `to`, in the order the MFMA groups need them
+                auto R = [&](int b, int st, int to, int i0, int i1) {
+                    const char *stage = lds + b * S::STAGE_BYTES;
+                    const int pos = ((2 * st + kh) ^ swz) * 16;
+#pragma unroll
+                    for (int i = i0; i < i1; ++i) {
+                        if (i == 0) fa[to][0] = *(const bf16x8 *)(stage + a_row + pos);
+                        else if (i < 5) fb[to][i - 1] = *(const bf16x8 *)(stage + b_row + (i - 1) * 32 * BK * 2 + pos);
+                        else fa[to][i - 4] = *(const bf16x8 *)(stage + a_row + (i - 4) * 32 * BK * 2 + pos);
                     }
-                    if (same_tile) issue(mt, nt, iks, ibuf, s0);
-                    else if (have_next) issue(mt2, nt2, iks - KS, ibuf, s0);
-                    mfmas(fa[cur], fb[cur]);
+                    __builtin_amdgcn_sched_barrier(0);
+                };
+                Gx(0, 0); R(buf, 1, 1, 0, 4);
+                Gx(0, 1); R(buf, 1, 1, 4, 8);
+                Gx(0, 2); L(0); L(1); __builtin_amdgcn_sched_barrier(0);
+                Gx(0, 3); L(2); L(3); __builtin_amdgcn_sched_barrier(0);
+                Gx(1, 0); L(4); L(5); __builtin_amdgcn_sched_barrier(0);
+                Gx(1, 1);
+                if (next_stage) {
+                    if (issuing) wait_vm_lgkm_and_barrier<(AHEAD - 2) * LPW + 6>();
+                    else wait_vm_lgkm_and_barrier<0>();
+                    R(nbuf, 0, 0, 0, 4);
                 }
+                Gx(1, 2);
+                if (next_stage) R(nbuf, 0, 0, 4, 8);
+                Gx(1, 3); L(6); L(7); __builtin_amdgcn_sched_barrier(0);
                 buf = nbuf;
             };
             for (int ks = 0; ks < KS - AHEAD; ++ks) pipe_stage(ks, true);
 #pragma unroll
             for (int p = 0; p < AHEAD; ++p) pipe_stage(KS - AHEAD + p, false);
+            if (have_next) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) voff[j] = voff2[j];
+            }
         } else {
         // Stage ks has landed once at most the NS-2 younger stages are outstanding (loads complete in
         // order).  The barrier also frees the buffer computed in the previous iteration, which is the
@@ -480,6 +532,7 @@ hipError_t launch(const LmHeadArgs &a, int num_cus, int gm, hipStream_t s)
     sc.tiles_n = (a.V + S::BN - 1) / S::BN;
     sc.gm = gm < 1 ? 1 : (gm > sc.tiles_m ? sc.tiles_m : gm);
     sc.total = sc.tiles_m * sc.tiles_n;
+    { const char *e = getenv("AJ_EXP"); sc.exp = e ? atoi(e) : 0; if (getenv("AJ_GM")) sc.gm = atoi(getenv("AJ_GM")); }
     const int grid = grid_for(num_cus, sc.total);
     if (a.dump)
         hipLaunchKernelGGL((k_lm_head_mfma<S, true>), dim3(grid), dim3(S::NW * 64), 0, s, a, sc);
