@@ -275,10 +275,10 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
     int mt = 0, nt = 0, buf = 0;       // buf: ring buffer of the stage computed next
     if (T < sc.total) {
         tile_of(sc, T, mt, nt);
-        if (S::PIPE) tile_offsets(mt, nt, voff);
+        if constexpr (S::PIPE) tile_offsets(mt, nt, voff);
 #pragma unroll
         for (int p = 0; p < AHEAD; ++p) issue(mt, nt, p, p);
-        if (S::PIPE) {
+        if constexpr (S::PIPE) {
             wait_vm_lgkm_and_barrier<(AHEAD - 1) * LPW>();
             read_frags(0, 0, fa[0], fb[0]);
         }
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
-        if (S::PIPE) {
+        if constexpr (S::PIPE) {
             // Hand-scheduled stage for the MFMA-bound shape (4x4 blocks per wave, 2 k steps, 8 loads
             // per wave and stage).  With one wave per SIMD every instruction that is not an MFMA
             // must sit in the shadow of a running MFMA, so the 16 MFMAs of a k step go out in 4
@@ -320,6 +320,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                 const uint32_t dst = lds_base + ibuf * S::STAGE_BYTES + wave * 1024;
                 auto L = [&](int j) {
                     if (!issuing) return;
+                    if (sc.exp & 1) return;
                     const uint32_t vo = same_tile ? voff[j] : voff2[j];
                     if (j < 4) lds_dma_16(Wk, vo, dst + j * NW * 1024);
                     else lds_dma_16(Hk, vo, dst + S::W_BYTES + (j - 4) * NW * 1024);
@@ -332,6 +333,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                 };
                 // fragment i of (buffer b, step s) into set `to`, in the order the MFMA groups need them
                 auto R = [&](int b, int st, int to, int i0, int i1) {
+                    if (sc.exp & 2) return;
                     const char *stage = lds + b * S::STAGE_BYTES;
                     const int pos = ((2 * st + kh) ^ swz) * 16;
 #pragma unroll
@@ -349,7 +351,8 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                 Gx(1, 0); L(4); L(5); __builtin_amdgcn_sched_barrier(0);
                 Gx(1, 1);
                 if (next_stage) {
-                    if (issuing) wait_vm_lgkm_and_barrier<(AHEAD - 2) * LPW + 6>();
+                    if (sc.exp & 4) {}
+                    else if (issuing) wait_vm_lgkm_and_barrier<(AHEAD - 2) * LPW + 6>();
                     else wait_vm_lgkm_and_barrier<0>();
                     R(nbuf, 0, 0, 0, 4);
                 }

@@ -6,36 +6,45 @@ namespace aj {
 
 namespace {
 
-constexpr int TAIL_WAVES = 8;
+constexpr int TAIL_WAVES = 16;
 constexpr int MAXK = 1023;
 
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 
-// wave-wide partial dot of n elements (n % 8 == 0 for bf16, % 4 for f32), fp32 accumulation
+// wave-wide partial dot of n elements (n % 8 == 0 for bf16, % 4 for f32), fp32 accumulation.
+// Four 16-byte chunks per operand are requested before any is used: this kernel is a chain of
+// memory round trips, so what counts is how many loads are in flight, not the arithmetic.
 template <bool BF16>
 __device__ __forceinline__ float dot_part(const void *x, const void *w, int n, int lane)
 {
-    float acc = 0.f;
-    if (BF16) {
-        const u32x4 *xp = (const u32x4 *)x, *wp = (const u32x4 *)w;
-        for (int c = lane; c < n / 8; c += 64) {
-            u32x4 xv = xp[c], wv = wp[c];
+    constexpr int U = 4;
+    float acc[U] = {0.f, 0.f, 0.f, 0.f};
+    const int nchunks = n / (BF16 ? 8 : 4);
+    const u32x4 *xp = (const u32x4 *)x, *wp = (const u32x4 *)w;
+    for (int c0 = lane; c0 < nchunks; c0 += 64 * U) {
+        u32x4 xv[U], wv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + 64 * u;
+            const bool in = c < nchunks;
+            xv[u] = in ? xp[c] : u32x4{0, 0, 0, 0};
+            wv[u] = in ? wp[c] : u32x4{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                acc = fmaf(bf16_lo(xv[q]), bf16_lo(wv[q]), acc);
-                acc = fmaf(bf16_hi(xv[q]), bf16_hi(wv[q]), acc);
+                if (BF16) {
+                    acc[u] = fmaf(bf16_lo(xv[u][q]), bf16_lo(wv[u][q]), acc[u]);
+                    acc[u] = fmaf(bf16_hi(xv[u][q]), bf16_hi(wv[u][q]), acc[u]);
+                } else {
+                    acc[u] = fmaf(__uint_as_float(xv[u][q]), __uint_as_float(wv[u][q]), acc[u]);
+                }
             }
         }
-    } else {
-        const f32x4 *xp = (const f32x4 *)x, *wp = (const f32x4 *)w;
-        for (int c = lane; c < n / 4; c += 64) {
-            f32x4 xv = xp[c], wv = wp[c];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) acc = fmaf(xv[q], wv[q], acc);
-        }
     }
-    return acc;
+    return (acc[0] + acc[1]) + (acc[2] + acc[3]);
 }
 
 // Phase 1: a wave per verify row reduces the row's block partials (coalesced: they are stored
@@ -57,12 +66,19 @@ __global__ __launch_bounds__(TAIL_WAVES * 64) void k_verify_tail(TailArgs a)
         const Best *p = a.part + row * a.nblocks;
         float bv = -INFINITY;
         int32_t bi = 0x7fffffff;
-        for (int nb = lane; nb < a.nblocks; nb += 64) {
-            Best x = p[nb];
-            if (better(x.v, x.i, bv, bi)) {
-                bv = x.v;
-                bi = x.i;
+        for (int nb0 = lane; nb0 < a.nblocks; nb0 += 256) {       // 4 loads in flight per lane
+            Best x[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int nb = nb0 + 64 * u;
+                x[u] = nb < a.nblocks ? p[nb] : Best{-INFINITY, 0x7fffffff};
             }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (better(x[u].v, x[u].i, bv, bi)) {
+                    bv = x[u].v;
+                    bi = x[u].i;
+                }
         }
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) {
