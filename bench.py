@@ -37,6 +37,9 @@ def main():
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--kernel", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="instead of the benchmark: a plain device copy of 1 GiB, repeated --steps times "
+                         "(the known-size kernel that HBM byte counters are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -45,6 +48,16 @@ def main():
 
     import numpy as np
     import torch
+    if args.copy_calibration:
+        n = 1 << 30
+        src = torch.ones(n, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n,
+                          "launches": args.steps}))
+        return
     import workloads as wl
     import paper_2504_20039_amd as aj
 
