@@ -24,7 +24,6 @@
 //   BIG     256 x 256, BK = 64, 2 stages: MFMA-bound regime
 #include "../../include/aj.h"
 #include "aj_internal.h"
-#include <stdlib.h>
 
 namespace aj {
 
@@ -115,7 +114,6 @@ using BigShape = Shape<4, 4, 2, 2, 1, 32, 4, false, 0, true>;
 
 struct Sched {
     int tiles_m, tiles_n, gm, total;
-    int exp;   // TEMP
 };
 
 __device__ __forceinline__ void tile_of(const Sched &sc, int T, int &mt, int &nt)
@@ -186,7 +184,6 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
 #pragma unroll
         for (int j = 0; j < LPW; ++j) {
             if (part >= 0 && j / S::LPP != part) continue;
-            if (sc.exp & 1) continue;
             if (j < S::WI / NW) {
                 const int row = min(n_first + j * NW * RPI, a.V - 1);       // clamped: ragged tiles stay in bounds
                 load_to_lds_16(W, __umul24(row, rowbytes) + koff, stage + j * NW * 1024);
@@ -252,7 +249,6 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
     // PIPE: two fragment sets
     bf16x8 fa[2][TN], fb[2][TM];
     auto read_frags = [&](int buf, int s, bf16x8(&ra)[TN], bf16x8(&rb)[TM]) {
-        if (sc.exp & 2) return;
         const char *stage = lds + buf * S::STAGE_BYTES;
         const int pos = ((2 * s + kh) ^ swz) * 16;
 #pragma unroll
@@ -320,7 +316,6 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                 const uint32_t dst = lds_base + ibuf * S::STAGE_BYTES + wave * 1024;
                 auto L = [&](int j) {
                     if (!issuing) return;
-                    if (sc.exp & 1) return;
                     const uint32_t vo = same_tile ? voff[j] : voff2[j];
                     if (j < 4) lds_dma_16(Wk, vo, dst + j * NW * 1024);
                     else lds_dma_16(Hk, vo, dst + S::W_BYTES + (j - 4) * NW * 1024);
@@ -333,8 +328,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                 };
                 // fragment i of (buffer b, step s) into set `to`, in the order the MFMA groups need them
                 auto R = [&](int b, int st, int to, int i0, int i1) {
-                    if (sc.exp & 2) return;
-                    const char *stage = lds + b * S::STAGE_BYTES;
+                                const char *stage = lds + b * S::STAGE_BYTES;
                     const int pos = ((2 * st + kh) ^ swz) * 16;
 #pragma unroll
                     for (int i = i0; i < i1; ++i) {
@@ -351,8 +345,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                 Gx(1, 0); L(4); L(5); __builtin_amdgcn_sched_barrier(0);
                 Gx(1, 1);
                 if (next_stage) {
-                    if (sc.exp & 4) {}
-                    else if (issuing) wait_vm_lgkm_and_barrier<(AHEAD - 2) * LPW + 6>();
+                    if (issuing) wait_vm_lgkm_and_barrier<(AHEAD - 2) * LPW + 6>();
                     else wait_vm_lgkm_and_barrier<0>();
                     R(nbuf, 0, 0, 0, 4);
                 }
@@ -535,7 +528,6 @@ hipError_t launch(const LmHeadArgs &a, int num_cus, int gm, hipStream_t s)
     sc.tiles_n = (a.V + S::BN - 1) / S::BN;
     sc.gm = gm < 1 ? 1 : (gm > sc.tiles_m ? sc.tiles_m : gm);
     sc.total = sc.tiles_m * sc.tiles_n;
-    { const char *e = getenv("AJ_EXP"); sc.exp = e ? atoi(e) : 0; if (getenv("AJ_GM")) sc.gm = atoi(getenv("AJ_GM")); }
     const int grid = grid_for(num_cus, sc.total);
     if (a.dump)
         hipLaunchKernelGGL((k_lm_head_mfma<S, true>), dim3(grid), dim3(S::NW * 64), 0, s, a, sc);
