@@ -70,7 +70,7 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
     if (c.B < 0 || c.K < 1 || c.K > 1023 || c.V < 1 || c.d_t < mult || c.d_d < 0) return AJ_EINVAL;
     if (c.d_t % mult || c.d_d % mult) return AJ_EINVAL;
     if (c.feat_offset != 0 && c.feat_offset != 1) return AJ_EINVAL;
-    if (c.kernel < AJ_KERNEL_AUTO || c.kernel > AJ_KERNEL_BIG) return AJ_EINVAL;
+    if (c.kernel < AJ_KERNEL_AUTO || c.kernel > AJ_KERNEL_TALL) return AJ_EINVAL;
     if ((int64_t)c.B * (c.K + 1) > (int64_t)1 << 24) return AJ_EINVAL;
 
     aj_handle *h = new (std::nothrow) aj_handle();
@@ -97,9 +97,12 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
     } else {
         int v = c.kernel;
         if (v == AJ_KERNEL_AUTO) {
-            // W_lm-streaming regime while one 32-row block holds every verify row; the large-tile
-            // kernel once the rows fill a good part of its 256-row tile; the general kernel otherwise
+            // W_lm-streaming regime while one 32-row block holds every verify row; a 128x320 tile that
+            // reads W_lm once when 257..320 rows would otherwise spill into a second, nearly empty row
+            // tile; the large-tile kernel once the rows fill a good part of its 256-row tile; the
+            // general kernel otherwise
             if (lm_head_mfma_supports(AJ_KERNEL_STREAM, h->M, c.V, c.d_t)) v = AJ_KERNEL_STREAM;
+            else if (h->M > 256 && lm_head_mfma_supports(AJ_KERNEL_TALL, h->M, c.V, c.d_t)) v = AJ_KERNEL_TALL;
             else if (h->M >= 192 && lm_head_mfma_supports(AJ_KERNEL_BIG, h->M, c.V, c.d_t)) v = AJ_KERNEL_BIG;
             else v = AJ_KERNEL_TILE;
         } else if (v != AJ_KERNEL_TILE && h->M > 0 && !lm_head_mfma_supports(v, h->M, c.V, c.d_t)) {
@@ -274,6 +277,7 @@ extern "C" const char *aj_kernel_name(const aj_handle *h)
         case AJ_KERNEL_TILE: return "lm_head_tile_bf16";
         case AJ_KERNEL_STREAM: return "lm_head_stream_bf16";
         case AJ_KERNEL_BIG: return "lm_head_big_bf16";
+        case AJ_KERNEL_TALL: return "lm_head_tall_bf16";
         default: return "unknown";
     }
 }

@@ -90,27 +90,43 @@ struct Shape {
     static constexpr int SWM = CH >= 16 ? 16 : CH;       // swizzle modulus: XOR acts on the low bits of the chunk index
     static constexpr int KSTEPS = BK / 16 / WK;   // k16 steps per wave per stage
     static constexpr int WI = BN / RPI, HI = HREG ? 0 : BM / RPI;   // wave-wide loads per stage: W tile, H tile
-    static constexpr int LPW = (WI + HI) / NW;    // loads per wave per stage
+    static constexpr int HLW = (HI + NW - 1) / NW;   // H loads per wave (when HI % NW != 0 the last waves repeat a load)
+    static constexpr int LPW = WI / NW + HLW;     // loads per wave per stage
     static constexpr int W_BYTES = BN * BK * 2, H_BYTES = HREG ? 0 : BM * BK * 2;
     static constexpr int STAGE_BYTES = W_BYTES + H_BYTES;
     static constexpr int RED_BYTES = (WK - 1) * WN * WM * TN * TM * 16 * 64 * 4;   // k-split partial sums
     static_assert(CH == 4 || CH == 8 || CH == 16 || CH == 32, "BK must be 32, 64, 128 or 256");
-    static_assert(WI % NW == 0 && HI % NW == 0, "loads must split evenly over the waves");
+    static_assert(WI % NW == 0, "W loads must split evenly over the waves");
     static_assert((BK / 16) % WK == 0, "k steps must split evenly over the k-split waves");
     static_assert((NW * RPI) % 16 == 0, "the chunk a lane fetches must not depend on the load index");
     static_assert((NS - 2) * LPW <= 63, "vmcnt range");
     static_assert(NS * STAGE_BYTES + BM * WN * 8 + RED_BYTES <= 160 * 1024, "LDS budget");
     static_assert(!HREG || (TM == 1 && WM == 1 && RUNNING), "register-resident hidden_t: one 32-row block");
     static constexpr int LPP = LPW / KSTEPS;      // PIPE: loads per wave per k step
-    static_assert(!PIPE || (!HREG && WK == 1 && NS >= 3 && KSTEPS == 2 && TN == 4 && TM == 4 && WI / NW == 4 &&
-                            HI / NW == 4),
-                  "hand-scheduled stage: 4x4 blocks, 2 k steps, 4 + 4 loads per wave");
-    static_assert(!PIPE || (NS - 3) * LPW + 6 <= 63, "vmcnt range");
+    // PIPE schedule.  The TN*TM MFMAs of a k step go out in NG groups (x-major order); a "slot" is the
+    // shadow of one group.  Fragment reads of the next step (TN + TM of them, in the order fa0, fb0..,
+    // fa1.. that the first groups need) follow groups 0 and 1, or groups 1 and 2 in a stage's last
+    // step, where the wait + barrier for the next stage comes right after group 1.  The stage's LPW
+    // loads are spread evenly over all KSTEPS*NG slots.
+    static constexpr int NG = (TN * TM) % 4 == 0 ? 4 : 5;          // 4x4 blocks: 4 groups of 4; 2x5: 5 groups of 2
+    static constexpr int GS = TN * TM / NG;
+    static constexpr int SLOTS = KSTEPS * NG;
+    static constexpr int NR = TN + TM, NR0 = (NR + 1) / 2;          // reads: first chunk, then the rest
+    static constexpr int loads_begin(int slot) { return (slot * LPW + SLOTS - 1) / SLOTS; }   // ceil(slot*LPW/SLOTS)
+    static constexpr int loads_end(int slot) { return ((slot + 1) * LPW + SLOTS - 1) / SLOTS; }
+    // loads of the stage being issued that precede the barrier (those in slots up to the last step's group 0)
+    static constexpr int LOADS_BEFORE_BARRIER = loads_end((KSTEPS - 1) * NG);
+    static constexpr int PIPE_VMCNT = NS == 2 ? 0 : (NS - 3) * LPW + LOADS_BEFORE_BARRIER;
+    static_assert(!PIPE || (!HREG && WK == 1 && NS >= 2 && KSTEPS >= 2 && KSTEPS % 2 == 0 && (TN * TM) % NG == 0 && NG >= 3),
+                  "hand-scheduled stage: even number of k steps (two fragment sets alternate), at least 3 groups");
+    static_assert(!PIPE || NS > 2 || LOADS_BEFORE_BARRIER == LPW, "two stages: the whole next stage precedes the barrier");
+    static_assert(!PIPE || PIPE_VMCNT <= 63, "vmcnt range");
 };
 
 using StreamShape = Shape<1, 1, 4, 1, 1, 128, 3, true>;            // any d_t % 128 == 0
 using Stream4096Shape = Shape<1, 1, 1, 1, 8, 256, 8, true, 16>;     // d_t == 4096, hidden_t in registers
 using BigShape = Shape<4, 4, 2, 2, 1, 32, 4, false, 0, true>;
+using TallShape = Shape<2, 5, 4, 2, 1, 32, 4, false>;               // 256 x 320, 8 waves: 257..320 verify rows in ONE row tile
 
 struct Sched {
     int tiles_m, tiles_n, gm, total;
@@ -188,9 +204,13 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                 const int row = min(n_first + j * NW * RPI, a.V - 1);       // clamped: ragged tiles stay in bounds
                 load_to_lds_16(W, __umul24(row, rowbytes) + koff, stage + j * NW * 1024);
             } else {
-                const int jj = j - S::WI / NW;
+                // H load jj of this wave is tile load jj*NW + wave; a wave that has none left (HI is not a
+                // multiple of NW) repeats its previous one: same rows to the same place, harmless
+                int jj = j - S::WI / NW;
+                if (jj * NW + wave >= S::HI) jj -= 1;
                 const int row = min(m_first + jj * NW * RPI, a.M - 1);
-                load_to_lds_16(H, __umul24(row, rowbytes) + koff, stage + S::W_BYTES + jj * NW * 1024);
+                load_to_lds_16(H, __umul24(row, rowbytes) + koff,
+                               __builtin_amdgcn_readfirstlane(stage + S::W_BYTES + jj * NW * 1024));
             }
         }
     };
@@ -256,14 +276,18 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
 #pragma unroll
         for (int y = 0; y < TM; ++y) rb[y] = *(const bf16x8 *)(stage + b_row + y * 32 * BK * 2 + pos);
     };
-    // PIPE: lane offsets of the 8 loads of a stage, fixed per tile (4 W_lm rows, 4 hidden_t rows)
-    uint32_t voff[8];
-    auto tile_offsets = [&](int mt_, int nt_, uint32_t(&vo)[8]) {
+    // PIPE: lane offsets of the loads of a stage, fixed per tile
+    constexpr int WL = S::WI / NW;     // loads 0..WL-1 fetch W_lm rows, the rest hidden_t rows
+    uint32_t voff[LPW];
+    auto tile_offsets = [&](int mt_, int nt_, uint32_t(&vo)[LPW]) {
         const int n_first = nt_ * S::BN + wave * RPI + rl, m_first = mt_ * S::BM + wave * RPI + rl;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            vo[j] = __umul24(min(n_first + j * NW * RPI, a.V - 1), rowbytes) + cg16;
-            vo[4 + j] = __umul24(min(m_first + j * NW * RPI, a.M - 1), rowbytes) + cg16;
+        for (int j = 0; j < LPW; ++j) {
+            if (j < WL) vo[j] = __umul24(min(n_first + j * NW * RPI, a.V - 1), rowbytes) + cg16;
+            else {
+                static_assert(!S::PIPE || S::HI % NW == 0, "hand-scheduled path: H loads split evenly");
+                vo[j] = __umul24(min(m_first + (j - WL) * NW * RPI, a.M - 1), rowbytes) + cg16;
+            }
         }
     };
 
@@ -293,17 +317,18 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                 for (int r = 0; r < 16; ++r) acc[x][y][r] = 0.f;
 
         if constexpr (S::PIPE) {
-            // Hand-scheduled stage for the MFMA-bound shape (4x4 blocks per wave, 2 k steps, 8 loads
-            // per wave and stage).  With one wave per SIMD every instruction that is not an MFMA
-            // must sit in the shadow of a running MFMA, so the 16 MFMAs of a k step go out in 4
-            // groups of 4 (128 cycles each) and at most 4 LDS reads or 2 loads follow each group;
-            // sched_barrier pins that order.  Fragments of (stage ks, step 0) are already in set 0
-            // (read after the previous stage's early barrier).
-            //   step 0:  G0 r r r r | G1 r r r r | G2 L L | G3 L L          (reads: step 1 of this stage)
-            //   step 1:  G0 L L | G1 wait+barrier r r r r | G2 r r r r | G3 L L   (reads: step 0 of stage ks+1)
-            // At the barrier the loads younger than stage ks+1 are AHEAD-2 whole stages plus 6 of the
-            // stage being issued.  Without a next tile fewer loads are in flight: wait for all.
-            uint32_t voff2[8];
+            // Hand-scheduled stage for the MFMA-bound shapes (4x4 blocks per wave).  With one wave per
+            // SIMD every instruction that is not an MFMA must sit in the shadow of a running MFMA, so
+            // the 16 MFMAs of a k step go out in 4 groups of 4 (128 cycles each) and a few LDS reads
+            // or loads follow each group; sched_barrier pins that order.  Fragments of (stage ks,
+            // step 0) are already in set 0 (read after the previous stage's early barrier).  Per k step
+            // t: groups 0 and 1 are followed by the 8 fragment reads of step t+1; in the LAST step
+            // group 1 is followed by the wait + barrier for stage ks+1, and the reads (that stage's
+            // step 0) follow groups 1 and 2.  Loads of the stage being issued follow the groups given by S::loads_after.
+            // At the barrier the loads younger than stage ks+1 are AHEAD-2 whole stages plus those of
+            // the stage being issued that precede the barrier (AHEAD = 1: it IS stage ks+1, and all
+            // of it precedes the barrier).  Without a next tile fewer loads are in flight: wait for all.
+            uint32_t voff2[LPW];
             if (have_next) tile_offsets(mt2, nt2, voff2);
             auto pipe_stage = [&](int ks, bool hot) {
                 const int nbuf = buf + 1 == NS ? 0 : buf + 1;                       // next stage's buffer
@@ -314,44 +339,55 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                 const int iks = same_tile ? ks + AHEAD : ks + AHEAD - KS;           // stage being issued
                 const char *Wk = W + iks * BK * 2, *Hk = H + iks * BK * 2;
                 const uint32_t dst = lds_base + ibuf * S::STAGE_BYTES + wave * 1024;
-                auto L = [&](int j) {
-                    if (!issuing) return;
-                    const uint32_t vo = same_tile ? voff[j] : voff2[j];
-                    if (j < 4) lds_dma_16(Wk, vo, dst + j * NW * 1024);
-                    else lds_dma_16(Hk, vo, dst + S::W_BYTES + (j - 4) * NW * 1024);
-                };
-                auto Gx = [&](int cur, int x) {
+                auto L = [&](int j0, int j1) {
+                    if (issuing) {
 #pragma unroll
-                    for (int y = 0; y < TM; ++y)
-                        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][x], fb[cur][y], acc[x][y], 0, 0, 0);
+                        for (int j = j0; j < j1; ++j) {
+                            const uint32_t vo = same_tile ? voff[j] : voff2[j];
+                            if (j < WL) lds_dma_16(Wk, vo, dst + j * NW * 1024);
+                            else lds_dma_16(Hk, vo, dst + S::W_BYTES + (j - WL) * NW * 1024);
+                        }
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 };
-                // fragment i of (buffer b, step s) into set `to`, in the order the MFMA groups need them
+                auto Gx = [&](int cur, int g) {                   // MFMAs g*GS .. of the step, x-major
+#pragma unroll
+                    for (int m = g * S::GS; m < (g + 1) * S::GS; ++m)
+                        acc[m / TM][m % TM] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][m / TM], fb[cur][m % TM],
+                                                                                      acc[m / TM][m % TM], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                };
+                // fragments i0..i1 of (buffer b, step st) into set `to`, in the order fa0, fb0.., fa1..
                 auto R = [&](int b, int st, int to, int i0, int i1) {
-                                const char *stage = lds + b * S::STAGE_BYTES;
+                    const char *stage = lds + b * S::STAGE_BYTES;
                     const int pos = ((2 * st + kh) ^ swz) * 16;
 #pragma unroll
                     for (int i = i0; i < i1; ++i) {
                         if (i == 0) fa[to][0] = *(const bf16x8 *)(stage + a_row + pos);
-                        else if (i < 5) fb[to][i - 1] = *(const bf16x8 *)(stage + b_row + (i - 1) * 32 * BK * 2 + pos);
-                        else fa[to][i - 4] = *(const bf16x8 *)(stage + a_row + (i - 4) * 32 * BK * 2 + pos);
+                        else if (i <= TM) fb[to][i - 1] = *(const bf16x8 *)(stage + b_row + (i - 1) * 32 * BK * 2 + pos);
+                        else fa[to][i - TM] = *(const bf16x8 *)(stage + a_row + (i - TM) * 32 * BK * 2 + pos);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 };
-                Gx(0, 0); R(buf, 1, 1, 0, 4);
-                Gx(0, 1); R(buf, 1, 1, 4, 8);
-                Gx(0, 2); L(0); L(1); __builtin_amdgcn_sched_barrier(0);
-                Gx(0, 3); L(2); L(3); __builtin_amdgcn_sched_barrier(0);
-                Gx(1, 0); L(4); L(5); __builtin_amdgcn_sched_barrier(0);
-                Gx(1, 1);
-                if (next_stage) {
-                    if (issuing) wait_vm_lgkm_and_barrier<(AHEAD - 2) * LPW + 6>();
-                    else wait_vm_lgkm_and_barrier<0>();
-                    R(nbuf, 0, 0, 0, 4);
+#pragma unroll
+                for (int t = 0; t < S::KSTEPS; ++t) {
+                    const int cur = t & 1;
+                    const bool last = t == S::KSTEPS - 1;
+#pragma unroll
+                    for (int g = 0; g < S::NG; ++g) {
+                        Gx(cur, g);
+                        if (last && g == 1 && next_stage) {
+                            if (issuing) wait_vm_lgkm_and_barrier<S::PIPE_VMCNT>();
+                            else wait_vm_lgkm_and_barrier<0>();
+                        }
+                        const int rg = last ? g - 1 : g;          // 0: first chunk of reads, 1: second
+                        if (rg == 0 || rg == 1) {
+                            if (!last) R(buf, t + 1, cur ^ 1, rg ? S::NR0 : 0, rg ? S::NR : S::NR0);
+                            else if (next_stage) R(nbuf, 0, cur ^ 1, rg ? S::NR0 : 0, rg ? S::NR : S::NR0);
+                        }
+                        L(S::loads_begin(t * S::NG + g), S::loads_end(t * S::NG + g));
+                    }
                 }
-                Gx(1, 2);
-                if (next_stage) R(nbuf, 0, 0, 4, 8);
-                Gx(1, 3); L(6); L(7); __builtin_amdgcn_sched_barrier(0);
                 buf = nbuf;
             };
             for (int ks = 0; ks < KS - AHEAD; ++ks) pipe_stage(ks, true);
@@ -359,7 +395,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
             for (int p = 0; p < AHEAD; ++p) pipe_stage(KS - AHEAD + p, false);
             if (have_next) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) voff[j] = voff2[j];
+                for (int j = 0; j < LPW; ++j) voff[j] = voff2[j];
             }
         } else {
         // Stage ks has landed once at most the NS-2 younger stages are outstanding (loads complete in
@@ -547,6 +583,7 @@ int lm_head_mfma_blocks(int variant, int V, int d, int num_cus)
             return grid_for(num_cus, (V + Stream4096Shape::BN - 1) / Stream4096Shape::BN) * Stream4096Shape::WN;
         return grid_for(num_cus, (V + StreamShape::BN - 1) / StreamShape::BN) * StreamShape::WN;
     }
+    if (variant == AJ_KERNEL_TALL) return (V + TallShape::BN - 1) / TallShape::BN;
     return (V + BigShape::BN - 1) / BigShape::BN;
 }
 
@@ -560,6 +597,8 @@ bool lm_head_mfma_supports(int variant, int M, int V, int d)
     if (variant == AJ_KERNEL_STREAM)
         return d % StreamShape::BK == 0 && d / StreamShape::BK >= StreamShape::NS - 1 && M <= StreamShape::BM;
     if (variant == AJ_KERNEL_BIG) return d % BigShape::BK == 0 && d / BigShape::BK >= BigShape::NS - 1;
+    if (variant == AJ_KERNEL_TALL)
+        return d % TallShape::BK == 0 && d / TallShape::BK >= TallShape::NS - 1 && M <= TallShape::BM;
     return false;
 }
 
@@ -568,6 +607,7 @@ hipError_t lm_head_mfma_bf16(int variant, const LmHeadArgs &a, int num_cus, hipS
     if (a.M <= 0) return hipSuccess;
     if (variant == AJ_KERNEL_STREAM)
         return use_stream4096(a.d) ? launch<Stream4096Shape>(a, num_cus, 1, s) : launch<StreamShape>(a, num_cus, 1, s);
+    if (variant == AJ_KERNEL_TALL) return launch<TallShape>(a, num_cus, 1, s);
     return launch<BigShape>(a, num_cus, 8, s);
 }
 

@@ -9,7 +9,7 @@ from parity import compare, make_inputs, oracle_greedy, parity_case, run_gpu
 pytestmark = pytest.mark.gpu
 
 TINY = wl.WORKLOADS["tiny_f32"]
-KERNELS_BF16 = [1, 2, 3]          # AJ_KERNEL_TILE, _STREAM, _BIG (forced); 0 = AUTO is covered too
+KERNELS_BF16 = [1, 2, 3, 4]       # AJ_KERNEL_TILE, _STREAM, _BIG, _TALL (forced); 0 = AUTO is covered too
 
 
 def _skip_unless_supported(w, kernel):
