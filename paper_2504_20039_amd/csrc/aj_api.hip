@@ -11,6 +11,7 @@ struct aj_handle {
     aj_config cfg;
     int M;
     int variant;   // AJ_KERNEL_* actually used (for bf16), or -1 for the fp32 kernel
+    bool stream16; // AJ_KERNEL_STREAM served by the 16-row-tile kernel
     int nblocks;   // partials per verify row
     int device;
     int num_cus;
@@ -101,16 +102,21 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
             // reads W_lm once when 257..320 rows would otherwise spill into a second, nearly empty row
             // tile; the large-tile kernel once the rows fill a good part of its 256-row tile; the
             // general kernel otherwise
-            if (lm_head_mfma_supports(AJ_KERNEL_STREAM, h->M, c.V, c.d_t)) v = AJ_KERNEL_STREAM;
+            if (lm_head_stream16_supports(h->M, c.V, c.d_t) ||
+                lm_head_mfma_supports(AJ_KERNEL_STREAM, h->M, c.V, c.d_t)) v = AJ_KERNEL_STREAM;
             else if (h->M > 256 && lm_head_mfma_supports(AJ_KERNEL_TALL, h->M, c.V, c.d_t)) v = AJ_KERNEL_TALL;
             else if (h->M >= 192 && lm_head_mfma_supports(AJ_KERNEL_BIG, h->M, c.V, c.d_t)) v = AJ_KERNEL_BIG;
             else v = AJ_KERNEL_TILE;
-        } else if (v != AJ_KERNEL_TILE && h->M > 0 && !lm_head_mfma_supports(v, h->M, c.V, c.d_t)) {
+        } else if (v != AJ_KERNEL_TILE && h->M > 0 && !lm_head_mfma_supports(v, h->M, c.V, c.d_t) &&
+                   !(v == AJ_KERNEL_STREAM && lm_head_stream16_supports(h->M, c.V, c.d_t))) {
             delete h;
             return AJ_EINVAL;   // a forced variant that cannot run this shape
         }
         h->variant = v;
-        h->nblocks = v == AJ_KERNEL_TILE ? lm_head_tile_blocks(c.V) : lm_head_mfma_blocks(v, c.V, c.d_t, h->num_cus);
+        h->stream16 = v == AJ_KERNEL_STREAM && lm_head_stream16_supports(h->M, c.V, c.d_t);
+        h->nblocks = v == AJ_KERNEL_TILE ? lm_head_tile_blocks(c.V)
+                     : h->stream16     ? lm_head_stream16_blocks(c.V, h->num_cus)
+                                       : lm_head_mfma_blocks(v, c.V, c.d_t, h->num_cus);
     }
     if (h->M > 0) {
         const size_t np = (size_t)h->nblocks * h->M;
@@ -166,6 +172,7 @@ static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void 
     a.dump = dump;
     if (h->variant < 0) return lm_head_f32(a, s);
     if (h->variant == AJ_KERNEL_TILE) return lm_head_tile_bf16(a, s);
+    if (h->stream16) return lm_head_stream16_bf16(a, h->num_cus, s);
     return lm_head_mfma_bf16(h->variant, a, h->num_cus, s);
 }
 
@@ -275,7 +282,7 @@ extern "C" const char *aj_kernel_name(const aj_handle *h)
     switch (h->variant) {
         case -1: return "lm_head_f32";
         case AJ_KERNEL_TILE: return "lm_head_tile_bf16";
-        case AJ_KERNEL_STREAM: return "lm_head_stream_bf16";
+        case AJ_KERNEL_STREAM: return h->stream16 ? "lm_head_stream16_bf16" : "lm_head_stream_bf16";
         case AJ_KERNEL_BIG: return "lm_head_big_bf16";
         case AJ_KERNEL_TALL: return "lm_head_tall_bf16";
         default: return "unknown";

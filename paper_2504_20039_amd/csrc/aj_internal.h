@@ -43,6 +43,11 @@ hipError_t lm_head_tile_bf16(const LmHeadArgs &a, hipStream_t s);
 hipError_t lm_head_f32(const LmHeadArgs &a, hipStream_t s);
 hipError_t lm_head_mfma_bf16(int variant, const LmHeadArgs &a, int num_cus, hipStream_t s);
 
+// W_lm-streaming kernel with 16-row tiles and hidden_t in registers (M <= 32, d_t = 2048 or 4096)
+bool lm_head_stream16_supports(int M, int V, int d);
+int lm_head_stream16_blocks(int V, int num_cus);
+hipError_t lm_head_stream16_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s);
+
 struct TailArgs {
     const void *hidden_t, *hidden_d, *clf_w;
     const int32_t *draft_tok;

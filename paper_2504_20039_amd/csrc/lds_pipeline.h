@@ -1,0 +1,64 @@
+// Device helpers shared by the LM-head kernels that stream operand tiles global -> LDS asynchronously.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace aj {
+
+// Asynchronous 16-byte-per-lane load global -> LDS: lane i's data lands at lds_base + 16*i.
+// Written as inline assembly on purpose: with the compiler builtin, the compiler orders every later
+// LDS read after ALL outstanding loads of this kind (s_waitcnt vmcnt(0)), which would drain the
+// pipeline at every stage.  Here the kernel does its own accounting (wait_vm_and_barrier below); the
+// compiler sees only a memory clobber.  lds_dst must be wave-uniform (it travels in M0).
+__device__ __forceinline__ void load_to_lds_16(const char *base, uint32_t lane_off, uint32_t lds_dst)
+{
+    // base: wave-uniform global pointer; lane_off: this lane's unsigned byte offset from it
+    uint32_t saved_m0;   // M0 is reserved for the compiler: keep its value across the statement
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0)
+                 : "v"(lane_off), "s"(base), "s"(lds_dst)
+                 : "memory");
+}
+
+// Same load for the hand-scheduled loop: two instructions, M0 not restored (nothing else in these
+// kernels uses M0, and the compiler sets it itself before any use of its own).
+__device__ __forceinline__ void lds_dma_16(const char *base, uint32_t lane_off, uint32_t lds_dst)
+{
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(lds_dst) : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_offset_of(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char *)p;
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vm_and_barrier()
+{
+    // wait until at most N of this wave's global loads are outstanding, then workgroup barrier.
+    // The memory clobber keeps the compiler from moving LDS accesses across it.
+    static_assert(N >= 0 && N <= 63, "vmcnt field");
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vm_lgkm_and_barrier()
+{
+    // as above, and this wave's LDS reads have returned (its buffer may be overwritten after the barrier)
+    static_assert(N >= 0 && N <= 63, "vmcnt field");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+// grid of a persistent LM-head kernel: one workgroup per CU, a multiple of 8 (the XCD count), and no
+// more workgroups than tiles (rounded up to a multiple of 8 so that the tile -> XCD mapping holds)
+inline int persistent_grid(int num_cus, int total_tiles)
+{
+    int grid = (num_cus / 8) * 8;
+    if (grid < 8) grid = 8;
+    const int need = ((total_tiles + 7) / 8) * 8;
+    return grid > need ? need : grid;
+}
+
+}  // namespace aj

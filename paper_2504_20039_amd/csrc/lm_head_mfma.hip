@@ -24,49 +24,11 @@
 //   BIG     256 x 256, BK = 64, 2 stages: MFMA-bound regime
 #include "../../include/aj.h"
 #include "aj_internal.h"
+#include "lds_pipeline.h"
 
 namespace aj {
 
 namespace {
-
-typedef __attribute__((address_space(3))) void lds_void;
-typedef const __attribute__((address_space(1))) void gbl_void;
-
-// Asynchronous 16-byte-per-lane load global -> LDS: lane i's data lands at lds_base + 16*i.
-// Written as inline assembly on purpose: with the compiler builtin, the compiler orders every later
-// LDS read after ALL outstanding loads of this kind (s_waitcnt vmcnt(0)), which would drain the
-// pipeline at every stage.  Here the kernel does its own accounting (wait_vm_and_barrier below); the
-// compiler sees only a memory clobber.  lds_dst must be wave-uniform (it travels in M0).
-__device__ __forceinline__ void load_to_lds_16(const char *base, uint32_t lane_off, uint32_t lds_dst)
-{
-    // base: wave-uniform global pointer; lane_off: this lane's unsigned byte offset from it
-    uint32_t saved_m0;   // M0 is reserved for the compiler: keep its value across the statement
-    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
-                 : "=&s"(saved_m0)
-                 : "v"(lane_off), "s"(base), "s"(lds_dst)
-                 : "memory");
-}
-
-// Same load for the hand-scheduled loop: two instructions, M0 not restored (nothing else in these
-// kernels uses M0, and the compiler sets it itself before any use of its own).
-__device__ __forceinline__ void lds_dma_16(const char *base, uint32_t lane_off, uint32_t lds_dst)
-{
-    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(lds_dst) : "memory");
-}
-
-__device__ __forceinline__ uint32_t lds_offset_of(const void *p)
-{
-    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char *)p;
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vm_and_barrier()
-{
-    // wait until at most N of this wave's global loads are outstanding, then workgroup barrier.
-    // The memory clobber keeps the compiler from moving LDS accesses across it.
-    static_assert(N >= 0 && N <= 63, "vmcnt field");
-    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
-}
 
 template <int TN_, int TM_, int WN_, int WM_, int WK_, int BK_, int NS_, bool RUNNING_, int HREG_KS_ = 0, bool PIPE_ = false>
 struct Shape {
@@ -142,14 +104,6 @@ __device__ __forceinline__ void tile_of(const Sched &sc, int T, int &mt, int &nt
     const int g = (grp == ngroups - 1) ? sc.tiles_m - grp * sc.gm : sc.gm;
     mt = grp * sc.gm + within % g;
     nt = within / g;
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vm_lgkm_and_barrier()
-{
-    // as above, and this wave's LDS reads have returned (its buffer may be overwritten after the barrier)
-    static_assert(N >= 0 && N <= 63, "vmcnt field");
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
 template <class S, bool DUMP>
@@ -547,15 +501,6 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
     }
 }
 
-int grid_for(int num_cus, int total_tiles)
-{
-    int grid = (num_cus / 8) * 8;
-    if (grid < 8) grid = 8;
-    // no more workgroups than tiles (rounded up to the XCD count so that the run mapping holds)
-    const int need = ((total_tiles + 7) / 8) * 8;
-    return grid > need ? need : grid;
-}
-
 template <class S>
 hipError_t launch(const LmHeadArgs &a, int num_cus, int gm, hipStream_t s)
 {
@@ -564,7 +509,7 @@ hipError_t launch(const LmHeadArgs &a, int num_cus, int gm, hipStream_t s)
     sc.tiles_n = (a.V + S::BN - 1) / S::BN;
     sc.gm = gm < 1 ? 1 : (gm > sc.tiles_m ? sc.tiles_m : gm);
     sc.total = sc.tiles_m * sc.tiles_n;
-    const int grid = grid_for(num_cus, sc.total);
+    const int grid = persistent_grid(num_cus, sc.total);
     if (a.dump)
         hipLaunchKernelGGL((k_lm_head_mfma<S, true>), dim3(grid), dim3(S::NW * 64), 0, s, a, sc);
     else
@@ -580,8 +525,8 @@ int lm_head_mfma_blocks(int variant, int V, int d, int num_cus)
 {
     if (variant == AJ_KERNEL_STREAM) {  // one running partial per workgroup
         if (use_stream4096(d))
-            return grid_for(num_cus, (V + Stream4096Shape::BN - 1) / Stream4096Shape::BN) * Stream4096Shape::WN;
-        return grid_for(num_cus, (V + StreamShape::BN - 1) / StreamShape::BN) * StreamShape::WN;
+            return persistent_grid(num_cus, (V + Stream4096Shape::BN - 1) / Stream4096Shape::BN) * Stream4096Shape::WN;
+        return persistent_grid(num_cus, (V + StreamShape::BN - 1) / StreamShape::BN) * StreamShape::WN;
     }
     if (variant == AJ_KERNEL_TALL) return (V + TallShape::BN - 1) / TallShape::BN;
     return (V + BigShape::BN - 1) / BigShape::BN;

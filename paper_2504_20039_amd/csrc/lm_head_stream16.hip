@@ -1,0 +1,188 @@
+// LM head (step 1) + running greedy maximum (first half of step 2) for the W_lm-streaming regime:
+// at most 32 verify rows, d_t = 2048 or 4096.  HBM-bound: the only operand that moves is W_lm.
+//
+//   * hidden_t lives in REGISTERS for the whole kernel.  The 8 waves of a workgroup split the k range
+//     of every stage; a wave keeps the v_mfma_f32_16x16x32_bf16 B-fragments (column = verify row) of
+//     its own k sub-ranges: d_t/256 stages x 2 row blocks x 4 VGPRs = 128 VGPRs at d_t = 4096.
+//   * tiles of 16 vocabulary rows; a stage is 16 rows x 512 bytes = 8 KB, one direct-to-LDS load per
+//     wave; d_t/256 (= 16) stages in the ring, i.e. 120 KB of W_lm in flight per compute unit.  Few
+//     rows with long contiguous runs in flight is what the HBM likes best: on this chip a load-only
+//     kernel with this very pattern reads at 6.55 TB/s, with 32-row tiles at 6.1, with 128 rows x
+//     256 B at 5.0.
+//   * the ring has as many stages as a tile has k stages, so stage ks always sits in buffer ks and
+//     every LDS address in the unrolled loop is a compile-time constant.
+//   * per tile the 8 partial 16x32 logit blocks are added through LDS by wave 0, which keeps a
+//     running (max, lowest index) per lane; one partial per verify row and workgroup is written at
+//     the end.  Lane l of the MFMA result holds verify row l % 16 and vocabulary rows 4*(l/16)+r:
+//     ascending inside a lane and over a workgroup's tiles, so strict > keeps the lowest index.
+#include "../../include/aj.h"
+#include "aj_internal.h"
+#include "lds_pipeline.h"
+
+namespace aj {
+
+namespace {
+
+constexpr int S16_WAVES = 8;
+constexpr int S16_ROWS = 16;                 // vocabulary rows per tile
+constexpr int S16_SEG = 512;                 // bytes of each row per stage (256 k elements, 32 per wave)
+constexpr int S16_STAGE = S16_ROWS * S16_SEG;  // 8 KB = one 1 KB load per wave
+
+template <int KS, bool DUMP>   // d_t = KS * 256; ring of KS stages
+__global__ __launch_bounds__(S16_WAVES * 64) void k_lm_head_stream16(LmHeadArgs a, int ntiles)
+{
+    constexpr int NS = KS, AHEAD = NS - 1;
+    __shared__ __attribute__((aligned(1024))) char lds[NS * S16_STAGE];
+    __shared__ float redk[(S16_WAVES - 1) * 8 * 64];
+
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l16 = lane & 15, q4 = lane >> 4;
+    const char *W = (const char *)a.W, *H = (const char *)a.H;
+    const uint32_t rowbytes = (uint32_t)a.d * 2u;
+    const uint32_t lds_base = lds_offset_of(lds);
+
+    // persistent tile list: runs of (gridDim/8) consecutive tiles per XCD
+    const int G = gridDim.x, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, SL = G >> 3;
+    auto tile_at = [&](int step) { return (step * 8 + xcd) * SL + slot; };
+
+    // loader: this wave's load covers tile rows 2*wave, 2*wave+1; lane i fills slot (row i/32, chunk i%32)
+    // and fetches global chunk (i%32) ^ row (XOR swizzle on the low 4 bits: conflict-free fragment reads)
+    const int tr = 2 * wave + (lane >> 5);
+    const uint32_t cg16 = (uint32_t)(((lane & 31) ^ tr) * 16);
+    auto issue = [&](int tile, int ks) {          // stage ks of `tile` into buffer ks
+        const int row = min(tile * S16_ROWS + tr, a.V - 1);
+        lds_dma_16(W, __umul24(row, rowbytes) + (uint32_t)(ks * S16_SEG) + cg16,
+                   lds_base + ks * S16_STAGE + wave * 1024);
+    };
+    // A fragment (16 vocabulary rows x 32 k): lane (row l16, k group q4) reads chunk 4*wave + q4 of its row
+    const int a_off = l16 * S16_SEG + (((4 * wave + q4) ^ l16) * 16);
+
+    // hidden_t fragments: block b = verify rows 16b..16b+15 (clamped), k = ks*256 + wave*32 + q4*8 ..+8
+    bf16x8 hf[KS][2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const char *hrow = H + (size_t)min(b * 16 + l16, a.M - 1) * rowbytes;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) hf[ks][b] = *(const bf16x8 *)(hrow + (ks * 256 + wave * 32 + q4 * 8) * 2);
+    }
+    // make the compiler retire these loads here: its waits must not land inside the pipelined loop,
+    // where they would drain the kernel's own asynchronous loads
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(hf[ks][b]));
+
+    float run_v[2] = {-INFINITY, -INFINITY};
+    int32_t run_i[2] = {0x7fffffff, 0x7fffffff};
+
+    int T = tile_at(0);
+    if (T < ntiles) {
+#pragma unroll
+        for (int p = 0; p < AHEAD; ++p) issue(T, p);
+    }
+    for (int step = 0; T < ntiles; ++step) {
+        const int T2 = tile_at(step + 1);
+        const bool have_next = T2 < ntiles;
+        f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            // stage ks has landed once at most the NS-2 younger loads of this wave are outstanding; the
+            // barrier also frees buffer ks-1 (computed in the previous iteration) for the load issued
+            // now.  Without a next tile fewer loads are in flight: wait for all.
+            if (ks == 0) {
+                wait_vm_and_barrier<NS - 2>();
+                issue(T, AHEAD);                       // last stage of this tile into buffer NS-1
+            } else if (have_next) {
+                wait_vm_and_barrier<NS - 2>();
+                issue(T2, ks - 1);
+            } else {
+                wait_vm_and_barrier<0>();
+            }
+            const bf16x8 fa = *(const bf16x8 *)(lds + ks * S16_STAGE + a_off);
+            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, hf[ks][0], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, hf[ks][1], acc[1], 0, 0, 0);
+        }
+
+        // add the 8 waves' partial sums (wave 0 collects)
+        if (wave > 0) {
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) redk[(((wave - 1) * 2 + b) * 4 + r) * 64 + lane] = acc[b][r];
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        if (wave == 0) {
+#pragma unroll
+            for (int w = 1; w < S16_WAVES; ++w)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[b][r] += redk[(((w - 1) * 2 + b) * 4 + r) * 64 + lane];
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int v = T * S16_ROWS + q4 * 4 + r;
+                    if (v < a.V) {
+                        if (DUMP && b * 16 + l16 < a.M) a.dump[(size_t)(b * 16 + l16) * a.V + v] = acc[b][r];
+                        if (acc[b][r] > run_v[b]) {
+                            run_v[b] = acc[b][r];
+                            run_i[b] = v;
+                        }
+                    }
+                }
+        }
+        // redk is rewritten only after the KS stage barriers of the next tile
+        T = T2;
+    }
+
+    if (wave == 0) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            float bv = run_v[b];
+            int32_t bi = run_i[b];
+#pragma unroll
+            for (int off = 16; off <= 32; off <<= 1) {
+                const float ov = __shfl_xor(bv, off);
+                const int32_t oi = __shfl_xor(bi, off);
+                if (better(ov, oi, bv, bi)) {
+                    bv = ov;
+                    bi = oi;
+                }
+            }
+            const int row = b * 16 + l16;
+            if (q4 == 0 && row < a.M) a.part[(size_t)row * a.nblocks + blockIdx.x] = Best{bv, bi};
+        }
+    }
+}
+
+template <int KS>
+hipError_t launch16(const LmHeadArgs &a, int num_cus, hipStream_t s)
+{
+    const int ntiles = (a.V + S16_ROWS - 1) / S16_ROWS;
+    const int grid = persistent_grid(num_cus, ntiles);
+    if (a.dump)
+        hipLaunchKernelGGL((k_lm_head_stream16<KS, true>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
+    else
+        hipLaunchKernelGGL((k_lm_head_stream16<KS, false>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool lm_head_stream16_supports(int M, int V, int d)
+{
+    if (M <= 0 || M > 32 || V <= 0) return false;
+    if (d != 4096 && d != 2048) return false;
+    return (uint64_t)V * d * 2 < (1ull << 32) && V < (1 << 24);   // 32-bit lane offsets, 24-bit multiply
+}
+
+int lm_head_stream16_blocks(int V, int num_cus) { return persistent_grid(num_cus, (V + S16_ROWS - 1) / S16_ROWS); }
+
+hipError_t lm_head_stream16_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s)
+{
+    if (a.M <= 0) return hipSuccess;
+    return a.d == 4096 ? launch16<16>(a, num_cus, s) : launch16<8>(a, num_cus, s);
+}
+
+}  // namespace aj
