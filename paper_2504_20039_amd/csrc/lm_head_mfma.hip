@@ -15,13 +15,13 @@
 //     tiles go to the workgroups of one XCD (workgroup id mod 8), so that the 32 compute units
 //     behind one L2 work on a compact block of tiles that share operand panels.
 //
-// Two instantiations:
-//   STREAM  32 vocabulary x 32 verify rows per tile, BK = 256, 4 stages, the 4 waves split each
-//           stage's k range (partial sums are added through LDS once per tile).  Few rows with long
-//           contiguous segments in flight is what HBM wants: 2 KB of each W_lm row are in flight
-//           at a time.  Every workgroup keeps a running maximum over all its tiles and writes ONE
-//           partial per verify row.  W_lm-streaming (HBM-bound) regime, M <= 32.
-//   BIG     256 x 256, BK = 64, 2 stages: MFMA-bound regime
+// Three instantiations:
+//   STREAM  128 vocabulary x 32 verify rows, BK = 128, 3 stages, one running partial per workgroup and
+//           wave column: W_lm-streaming regime (M <= 32) at hidden sizes the register-resident
+//           16-row-tile kernel (lm_head_stream16.hip) does not take.
+//   BIG     256 x 256, 4 waves of 128 x 128, BK = 32, 4 stages, hand-scheduled stage: MFMA-bound regime.
+//   TALL    256 x 320, 8 waves of 64 x 160, BK = 32, 4 stages: 257..320 verify rows in ONE row tile, so
+//           that W_lm is read once and no nearly empty second row tile is computed.
 #include "../../include/aj.h"
 #include "aj_internal.h"
 #include "lds_pipeline.h"
@@ -30,15 +30,10 @@ namespace aj {
 
 namespace {
 
-template <int TN_, int TM_, int WN_, int WM_, int WK_, int BK_, int NS_, bool RUNNING_, int HREG_KS_ = 0, bool PIPE_ = false>
+template <int TN_, int TM_, int WN_, int WM_, int WK_, int BK_, int NS_, bool RUNNING_, bool PIPE_ = false>
 struct Shape {
     static constexpr int TN = TN_, TM = TM_, WN = WN_, WM = WM_, WK = WK_, BK = BK_, NS = NS_;
     static constexpr bool RUNNING = RUNNING_;     // one running partial per workgroup (needs a single row tile)
-    // HREG_KS > 0: the hidden_t operand lives in REGISTERS for the whole kernel (each k-split wave keeps
-    // the fragments of its own k sub-range of every stage), d_t is fixed at HREG_KS * BK, the k loop is
-    // unrolled, and LDS stages hold W_lm only.
-    static constexpr int HREG_KS = HREG_KS_;
-    static constexpr bool HREG = HREG_KS_ > 0;
     // PIPE: MFMA-bound schedule.  Fragments of k step s+1 are read while the MFMAs of step s run, the
     // stage's loads are issued in KSTEPS parts between them, and the wait + barrier for the NEXT
     // stage sits before the MFMAs of a stage's last k step, so the matrix pipe never waits for it.
@@ -51,10 +46,10 @@ struct Shape {
     static constexpr int RPW = CH >= 16 ? 1 : 16 / CH;   // tile rows per 256-byte bank wrap
     static constexpr int SWM = CH >= 16 ? 16 : CH;       // swizzle modulus: XOR acts on the low bits of the chunk index
     static constexpr int KSTEPS = BK / 16 / WK;   // k16 steps per wave per stage
-    static constexpr int WI = BN / RPI, HI = HREG ? 0 : BM / RPI;   // wave-wide loads per stage: W tile, H tile
+    static constexpr int WI = BN / RPI, HI = BM / RPI;   // wave-wide loads per stage: W tile, H tile
     static constexpr int HLW = (HI + NW - 1) / NW;   // H loads per wave (when HI % NW != 0 the last waves repeat a load)
     static constexpr int LPW = WI / NW + HLW;     // loads per wave per stage
-    static constexpr int W_BYTES = BN * BK * 2, H_BYTES = HREG ? 0 : BM * BK * 2;
+    static constexpr int W_BYTES = BN * BK * 2, H_BYTES = BM * BK * 2;
     static constexpr int STAGE_BYTES = W_BYTES + H_BYTES;
     static constexpr int RED_BYTES = (WK - 1) * WN * WM * TN * TM * 16 * 64 * 4;   // k-split partial sums
     static_assert(CH == 4 || CH == 8 || CH == 16 || CH == 32, "BK must be 32, 64, 128 or 256");
@@ -63,7 +58,6 @@ struct Shape {
     static_assert((NW * RPI) % 16 == 0, "the chunk a lane fetches must not depend on the load index");
     static_assert((NS - 2) * LPW <= 63, "vmcnt range");
     static_assert(NS * STAGE_BYTES + BM * WN * 8 + RED_BYTES <= 160 * 1024, "LDS budget");
-    static_assert(!HREG || (TM == 1 && WM == 1 && RUNNING), "register-resident hidden_t: one 32-row block");
     static constexpr int LPP = LPW / KSTEPS;      // PIPE: loads per wave per k step
     // PIPE schedule.  The TN*TM MFMAs of a k step go out in NG groups (x-major order); a "slot" is the
     // shadow of one group.  Fragment reads of the next step (TN + TM of them, in the order fa0, fb0..,
@@ -79,15 +73,14 @@ struct Shape {
     // loads of the stage being issued that precede the barrier (those in slots up to the last step's group 0)
     static constexpr int LOADS_BEFORE_BARRIER = loads_end((KSTEPS - 1) * NG);
     static constexpr int PIPE_VMCNT = NS == 2 ? 0 : (NS - 3) * LPW + LOADS_BEFORE_BARRIER;
-    static_assert(!PIPE || (!HREG && WK == 1 && NS >= 2 && KSTEPS >= 2 && KSTEPS % 2 == 0 && (TN * TM) % NG == 0 && NG >= 3),
+    static_assert(!PIPE || (WK == 1 && NS >= 2 && KSTEPS >= 2 && KSTEPS % 2 == 0 && (TN * TM) % NG == 0 && NG >= 3),
                   "hand-scheduled stage: even number of k steps (two fragment sets alternate), at least 3 groups");
     static_assert(!PIPE || NS > 2 || LOADS_BEFORE_BARRIER == LPW, "two stages: the whole next stage precedes the barrier");
     static_assert(!PIPE || PIPE_VMCNT <= 63, "vmcnt range");
 };
 
 using StreamShape = Shape<1, 1, 4, 1, 1, 128, 3, true>;            // any d_t % 128 == 0
-using Stream4096Shape = Shape<1, 1, 1, 1, 8, 256, 8, true, 16>;     // d_t == 4096, hidden_t in registers
-using BigShape = Shape<4, 4, 2, 2, 1, 32, 4, false, 0, true>;
+using BigShape = Shape<4, 4, 2, 2, 1, 32, 4, false, true>;
 using TallShape = Shape<2, 5, 4, 2, 1, 32, 4, false>;               // 256 x 320, 8 waves: 257..320 verify rows in ONE row tile
 
 struct Sched {
@@ -119,7 +112,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wn = wave % WN, wm = (wave / WN) % WM, wk = wave / (WN * WM);
     const int l32 = lane & 31, kh = lane >> 5;
-    const int d = a.d, KS = S::HREG ? S::HREG_KS : d / BK;       // host guarantees KS >= AHEAD
+    const int d = a.d, KS = d / BK;       // host guarantees KS >= AHEAD
     const char *W = (const char *)a.W, *H = (const char *)a.H;
 
     // ---- persistent tile list of this workgroup: runs of (gridDim/8) consecutive tiles per XCD
@@ -169,25 +162,6 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
         }
     };
 
-    // register-resident hidden_t fragments (B operand): column = verify row (clamped), this wave's k steps
-    bf16x8 hf[S::HREG ? S::HREG_KS : 1][S::HREG ? S::KSTEPS : 1];
-    if (S::HREG) {
-        const char *hrow = H + (size_t)min(l32, a.M - 1) * (size_t)(d * 2);
-#pragma unroll
-        for (int ks = 0; ks < (S::HREG ? S::HREG_KS : 1); ++ks)
-#pragma unroll
-            for (int s0 = 0; s0 < S::KSTEPS; ++s0)
-                hf[ks][s0] = *(const bf16x8 *)(hrow + (ks * BK + (wk * S::KSTEPS + s0) * 16 + kh * 8) * 2);
-        // These ordinary loads must be complete, and known to the compiler to be complete, before the
-        // first asynchronous load is issued: otherwise the waits the compiler places before their
-        // first use inside the pipelined loop would drain the kernel's own in-flight loads.  Touching
-        // every register in an (empty) asm statement makes the compiler wait here.
-#pragma unroll
-        for (int ks = 0; ks < (S::HREG ? S::HREG_KS : 1); ++ks)
-#pragma unroll
-            for (int s0 = 0; s0 < S::KSTEPS; ++s0) asm volatile("" : "+v"(hf[ks][s0]));
-    }
-
     f32x16 acc[TN][TM];
     float run_v[TM];
     int32_t run_i[TM];
@@ -209,8 +183,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
             for (int x = 0; x < TN; ++x) fa[x] = *(const bf16x8 *)(stage + a_row + x * 32 * BK * 2 + pos);
 #pragma unroll
             for (int y = 0; y < TM; ++y) {
-                if (S::HREG) fb[y] = hf[S::HREG ? ks : 0][s0];
-                else fb[y] = *(const bf16x8 *)(stage + b_row + y * 32 * BK * 2 + pos);
+                fb[y] = *(const bf16x8 *)(stage + b_row + y * 32 * BK * 2 + pos);
             }
 #pragma unroll
             for (int x = 0; x < TN; ++x)
@@ -355,21 +328,11 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
         // Stage ks has landed once at most the NS-2 younger stages are outstanding (loads complete in
         // order).  The barrier also frees the buffer computed in the previous iteration, which is the
         // one the new loads go to.  Hot part: the stage issued belongs to the same tile - no branches.
-        if (S::HREG) {
-#pragma unroll
-            for (int ks = 0; ks < (S::HREG ? S::HREG_KS - AHEAD : 0); ++ks) {
-                wait_vm_and_barrier<(NS - 2) * LPW>();
-                issue(mt, nt, ks + AHEAD, (buf + AHEAD) % NS);
-                compute(ks, buf);
-                buf = (buf + 1) % NS;
-            }
-        } else {
-            for (int ks = 0; ks < KS - AHEAD; ++ks) {
-                wait_vm_and_barrier<(NS - 2) * LPW>();
-                issue(mt, nt, ks + AHEAD, buf + AHEAD >= NS ? buf + AHEAD - NS : buf + AHEAD);
-                compute(ks, buf);
-                buf = buf + 1 == NS ? 0 : buf + 1;
-            }
+        for (int ks = 0; ks < KS - AHEAD; ++ks) {
+            wait_vm_and_barrier<(NS - 2) * LPW>();
+            issue(mt, nt, ks + AHEAD, buf + AHEAD >= NS ? buf + AHEAD - NS : buf + AHEAD);
+            compute(ks, buf);
+            buf = buf + 1 == NS ? 0 : buf + 1;
         }
         // Last AHEAD stages of the tile: prefetch the first stages of the next tile, if there is one;
         // otherwise fewer loads are in flight than the constant assumes, so wait for all of them.
@@ -381,7 +344,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
             } else {
                 wait_vm_and_barrier<0>();
             }
-            compute(S::HREG ? S::HREG_KS - AHEAD + p : KS - AHEAD + p, buf);
+            compute(KS - AHEAD + p, buf);
             buf = buf + 1 == NS ? 0 : buf + 1;
         }
         }
@@ -519,13 +482,9 @@ hipError_t launch(const LmHeadArgs &a, int num_cus, int gm, hipStream_t s)
 
 }  // namespace
 
-static bool use_stream4096(int d) { return d == Stream4096Shape::HREG_KS * Stream4096Shape::BK; }
-
 int lm_head_mfma_blocks(int variant, int V, int d, int num_cus)
 {
     if (variant == AJ_KERNEL_STREAM) {  // one running partial per workgroup
-        if (use_stream4096(d))
-            return persistent_grid(num_cus, (V + Stream4096Shape::BN - 1) / Stream4096Shape::BN) * Stream4096Shape::WN;
         return persistent_grid(num_cus, (V + StreamShape::BN - 1) / StreamShape::BN) * StreamShape::WN;
     }
     if (variant == AJ_KERNEL_TALL) return (V + TallShape::BN - 1) / TallShape::BN;
@@ -551,7 +510,7 @@ hipError_t lm_head_mfma_bf16(int variant, const LmHeadArgs &a, int num_cus, hipS
 {
     if (a.M <= 0) return hipSuccess;
     if (variant == AJ_KERNEL_STREAM)
-        return use_stream4096(a.d) ? launch<Stream4096Shape>(a, num_cus, 1, s) : launch<StreamShape>(a, num_cus, 1, s);
+        return launch<StreamShape>(a, num_cus, 1, s);
     if (variant == AJ_KERNEL_TALL) return launch<TallShape>(a, num_cus, 1, s);
     return launch<BigShape>(a, num_cus, 8, s);
 }
