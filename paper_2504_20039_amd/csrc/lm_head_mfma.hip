@@ -30,7 +30,7 @@ namespace aj {
 
 namespace {
 
-template <int TN_, int TM_, int WN_, int WM_, int WK_, int BK_, int NS_, bool RUNNING_, bool PIPE_ = false>
+template <int TN_, int TM_, int WN_, int WM_, int WK_, int BK_, int NS_, bool RUNNING_, bool PIPE_ = false, int MCUT_ = 0>
 struct Shape {
     static constexpr int TN = TN_, TM = TM_, WN = WN_, WM = WM_, WK = WK_, BK = BK_, NS = NS_;
     static constexpr bool RUNNING = RUNNING_;     // one running partial per workgroup (needs a single row tile)
@@ -40,7 +40,10 @@ struct Shape {
     static constexpr bool PIPE = PIPE_;
     static constexpr int NW = WN * WM * WK;       // waves per workgroup
     static constexpr int BN = 32 * TN * WN;       // vocabulary rows per tile
-    static constexpr int BM = 32 * TM * WM;       // verify rows per tile
+    // MCUT: the LAST wave row computes MCUT fewer 32-row blocks than the others (a tile of 9 blocks =
+    // 5 + 4), so that the tile height fits the row count more tightly
+    static constexpr int MCUT = MCUT_;
+    static constexpr int BM = 32 * (TM * WM - MCUT);   // verify rows per tile
     static constexpr int CH = BK / 8;             // 16-byte chunks per tile row
     static constexpr int RPI = 64 / CH;           // tile rows covered by one wave-wide load
     static constexpr int RPW = CH >= 16 ? 1 : 16 / CH;   // tile rows per 256-byte bank wrap
@@ -54,6 +57,7 @@ struct Shape {
     static constexpr int RED_BYTES = (WK - 1) * WN * WM * TN * TM * 16 * 64 * 4;   // k-split partial sums
     static_assert(CH == 4 || CH == 8 || CH == 16 || CH == 32, "BK must be 32, 64, 128 or 256");
     static_assert(WI % NW == 0, "W loads must split evenly over the waves");
+    static_assert(MCUT == 0 || (!PIPE_ && MCUT < TM && WM > 1), "short last wave row: compiler-scheduled path only");
     static_assert((BK / 16) % WK == 0, "k steps must split evenly over the k-split waves");
     static_assert((NW * RPI) % 16 == 0, "the chunk a lane fetches must not depend on the load index");
     static_assert((NS - 2) * LPW <= 63, "vmcnt range");
@@ -81,7 +85,8 @@ struct Shape {
 
 using StreamShape = Shape<1, 1, 4, 1, 1, 128, 3, true>;            // any d_t % 128 == 0
 using BigShape = Shape<4, 4, 2, 2, 1, 32, 4, false, true>;
-using TallShape = Shape<2, 5, 4, 2, 1, 32, 4, false>;               // 256 x 320, 8 waves: 257..320 verify rows in ONE row tile
+using TallShape = Shape<2, 5, 4, 2, 1, 64, 2, false>;                 // 256 x 320, 8 waves: 289..320 verify rows in ONE row tile
+using Tall288Shape = Shape<2, 5, 4, 2, 1, 64, 2, false, false, 1>;   // 256 x 288 (wave rows of 5 + 4 blocks)
 
 struct Sched {
     int tiles_m, tiles_n, gm, total;
@@ -172,6 +177,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
     }
 
     // MFMAs of one landed stage (ring buffer `buf`); this wave's share of the k steps
+    const int ty = (S::MCUT > 0 && wm == WM - 1) ? TM - S::MCUT : TM;   // 32-row blocks this wave computes (wave-uniform)
     auto compute = [&](int ks, int buf) {
         const char *stage = lds + buf * S::STAGE_BYTES;
 #pragma unroll
@@ -183,13 +189,13 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
             for (int x = 0; x < TN; ++x) fa[x] = *(const bf16x8 *)(stage + a_row + x * 32 * BK * 2 + pos);
 #pragma unroll
             for (int y = 0; y < TM; ++y) {
-                fb[y] = *(const bf16x8 *)(stage + b_row + y * 32 * BK * 2 + pos);
+                if (y < ty) fb[y] = *(const bf16x8 *)(stage + b_row + y * 32 * BK * 2 + pos);
             }
 #pragma unroll
             for (int x = 0; x < TN; ++x)
 #pragma unroll
                 for (int y = 0; y < TM; ++y)
-                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[x], fb[y], acc[x][y], 0, 0, 0);
+                    if (y < ty) acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[x], fb[y], acc[x][y], 0, 0, 0);
         }
     };
 
@@ -383,7 +389,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
 #pragma unroll
         for (int y = 0; y < TM; ++y) {
             const int lr = wm * TM * 32 + y * 32 + l32;          // verify row inside the tile
-            const int row = mt * S::BM + lr;
+            const int row = (y < ty) ? mt * S::BM + lr : a.M;    // a block this wave does not compute: no row
             float bv = S::RUNNING ? run_v[y] : -INFINITY;
             int32_t bi = S::RUNNING ? run_i[y] : 0x7fffffff;
 #pragma unroll
@@ -412,7 +418,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                 bv = ov;
                 bi = oi;
             }
-            if (WN > 1 && wn > 0 && kh == 0) red[(wn - 1) * S::BM + lr] = Best{bv, bi};
+            if (WN > 1 && wn > 0 && kh == 0 && y < ty) red[(wn - 1) * S::BM + lr] = Best{bv, bi};
             pv[y] = bv;
             pi[y] = bi;
         }
@@ -423,11 +429,11 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
 #pragma unroll
                 for (int y = 0; y < TM; ++y) {
                     const int lr = wm * TM * 32 + y * 32 + l32;
-                    const int row = mt * S::BM + lr;
+                    const int row = (y < ty) ? mt * S::BM + lr : a.M;
                     float bv = pv[y];
                     int32_t bi = pi[y];
 #pragma unroll
-                    for (int w = 1; w < WN; ++w) {
+                    for (int w = 1; w < WN && y < ty; ++w) {
                         const Best o = red[(w - 1) * S::BM + lr];
                         if (better(o.v, o.i, bv, bi)) {
                             bv = o.v;
@@ -511,7 +517,8 @@ hipError_t lm_head_mfma_bf16(int variant, const LmHeadArgs &a, int num_cus, hipS
     if (a.M <= 0) return hipSuccess;
     if (variant == AJ_KERNEL_STREAM)
         return launch<StreamShape>(a, num_cus, 1, s);
-    if (variant == AJ_KERNEL_TALL) return launch<TallShape>(a, num_cus, 1, s);
+    if (variant == AJ_KERNEL_TALL)
+        return a.M <= Tall288Shape::BM ? launch<Tall288Shape>(a, num_cus, 1, s) : launch<TallShape>(a, num_cus, 1, s);
     return launch<BigShape>(a, num_cus, 8, s);
 }
 
