@@ -98,14 +98,19 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
     } else {
         int v = c.kernel;
         if (v == AJ_KERNEL_AUTO) {
-            // W_lm-streaming regime while one 32-row block holds every verify row; a 128x320 tile that
-            // reads W_lm once when 257..320 rows would otherwise spill into a second, nearly empty row
-            // tile; the large-tile kernel once the rows fill a good part of its 256-row tile; the
-            // general kernel otherwise
+            // W_lm-streaming regime while one 32-row block holds every verify row.  From 192 rows on, one
+            // of the two large-tile kernels: 256-row tiles (4 waves, hand-scheduled) or 288/320-row tiles
+            // (8 waves), whichever rounds the row count up less - padded rows are wasted MFMA work, and a
+            // batch of 257..320 rows in ONE row tile also reads W_lm from HBM only once.  At equal padding
+            // the hand-scheduled 256-row kernel is about 4 % faster (measured on the same device), so the
+            // taller tiles must save more rows than that.  The general kernel otherwise.
+            const bool big = h->M >= 192 && lm_head_mfma_supports(AJ_KERNEL_BIG, h->M, c.V, c.d_t);
+            const bool tall = h->M >= 192 && lm_head_mfma_supports(AJ_KERNEL_TALL, h->M, c.V, c.d_t);
             if (lm_head_stream16_supports(h->M, c.V, c.d_t) ||
                 lm_head_mfma_supports(AJ_KERNEL_STREAM, h->M, c.V, c.d_t)) v = AJ_KERNEL_STREAM;
-            else if (h->M > 256 && lm_head_mfma_supports(AJ_KERNEL_TALL, h->M, c.V, c.d_t)) v = AJ_KERNEL_TALL;
-            else if (h->M >= 192 && lm_head_mfma_supports(AJ_KERNEL_BIG, h->M, c.V, c.d_t)) v = AJ_KERNEL_BIG;
+            else if (tall && (!big || 1.04 * lm_head_mfma_padded_rows(AJ_KERNEL_TALL, h->M) <
+                                          lm_head_mfma_padded_rows(AJ_KERNEL_BIG, h->M))) v = AJ_KERNEL_TALL;
+            else if (big) v = AJ_KERNEL_BIG;
             else v = AJ_KERNEL_TILE;
         } else if (v != AJ_KERNEL_TILE && h->M > 0 && !lm_head_mfma_supports(v, h->M, c.V, c.d_t) &&
                    !(v == AJ_KERNEL_STREAM && lm_head_stream16_supports(h->M, c.V, c.d_t))) {

@@ -37,6 +37,7 @@ int lm_head_tile_blocks(int V);
 int lm_head_f32_blocks(int V);
 int lm_head_mfma_blocks(int variant, int V, int d, int num_cus);  // variant: AJ_KERNEL_STREAM / AJ_KERNEL_BIG
 bool lm_head_mfma_supports(int variant, int M, int V, int d);
+int lm_head_mfma_padded_rows(int variant, int M);
 
 // Launchers return hipSuccess or the launch error.
 hipError_t lm_head_tile_bf16(const LmHeadArgs &a, hipStream_t s);

@@ -508,8 +508,17 @@ bool lm_head_mfma_supports(int variant, int M, int V, int d)
         return d % StreamShape::BK == 0 && d / StreamShape::BK >= StreamShape::NS - 1 && M <= StreamShape::BM;
     if (variant == AJ_KERNEL_BIG) return d % BigShape::BK == 0 && d / BigShape::BK >= BigShape::NS - 1;
     if (variant == AJ_KERNEL_TALL)
-        return d % TallShape::BK == 0 && d / TallShape::BK >= TallShape::NS - 1 && M <= TallShape::BM;
+        return d % TallShape::BK == 0 && d / TallShape::BK >= TallShape::NS - 1;
     return false;
+}
+
+// verify rows the variant computes for M rows (M rounded up to whole row tiles)
+int lm_head_mfma_padded_rows(int variant, int M)
+{
+    auto pad = [M](int bm) { return (M + bm - 1) / bm * bm; };
+    if (variant == AJ_KERNEL_TALL) return pad(Tall288Shape::BM) < pad(TallShape::BM) ? pad(Tall288Shape::BM) : pad(TallShape::BM);
+    if (variant == AJ_KERNEL_BIG) return pad(BigShape::BM);
+    return pad(StreamShape::BM);
 }
 
 hipError_t lm_head_mfma_bf16(int variant, const LmHeadArgs &a, int num_cus, hipStream_t s)
@@ -517,8 +526,12 @@ hipError_t lm_head_mfma_bf16(int variant, const LmHeadArgs &a, int num_cus, hipS
     if (a.M <= 0) return hipSuccess;
     if (variant == AJ_KERNEL_STREAM)
         return launch<StreamShape>(a, num_cus, 1, s);
-    if (variant == AJ_KERNEL_TALL)
-        return a.M <= Tall288Shape::BM ? launch<Tall288Shape>(a, num_cus, 1, s) : launch<TallShape>(a, num_cus, 1, s);
+    if (variant == AJ_KERNEL_TALL) {
+        // 288- or 320-row tiles, whichever pads the row count less (ties: the taller one, fewer tiles)
+        const int pad288 = (a.M + Tall288Shape::BM - 1) / Tall288Shape::BM * Tall288Shape::BM;
+        const int pad320 = (a.M + TallShape::BM - 1) / TallShape::BM * TallShape::BM;
+        return pad288 < pad320 ? launch<Tall288Shape>(a, num_cus, 8, s) : launch<TallShape>(a, num_cus, 8, s);
+    }
     return launch<BigShape>(a, num_cus, 8, s);
 }
 

@@ -50,6 +50,8 @@ def test_tiny_f32_workload_with_all_logits():
     dict(B=1, K=16, d_t=1024, d_d=256, V=5000),        # one skinny row block, several vocabulary tiles per CU
     dict(B=2, K=15, d_t=384, d_d=128, V=70000),        # M=32 exactly; more tiles than workgroups
     dict(B=20, K=31, d_t=512, d_d=64, V=3000),         # M=640: 3 row tiles x 12 column tiles of the large kernel
+    dict(B=10, K=31, d_t=256, d_d=64, V=1100),         # M=320: one 320-row tile of the 8-wave kernel
+    dict(B=19, K=31, d_t=128, d_d=64, V=600),          # M=608: two 320-row tiles vs three 256-row tiles
     dict(B=1, K=16, d_t=4096, d_d=256, V=5003),        # the register-resident streaming kernel, ragged vocabulary
     dict(B=2, K=15, d_t=2048, d_d=128, V=9000),        # ... at d_t = 2048, all 32 rows
     dict(B=1, K=4, d_t=4096, d_d=64, V=40),            # ... fewer tiles than workgroups
