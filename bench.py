@@ -31,8 +31,8 @@ def algorithmic(w, nblocks_bytes=0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="8b_b1_k16")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--kernel", type=int, default=0)
@@ -144,9 +144,12 @@ def main():
     # ---- the CPU oracle on the machine's host cores: a reported baseline, not the target
     if not args.no_cpu_baseline:
         import oracle
-        nwin = min(w.B, max(1, int(2.0e11 // (w.K + 1) // (w.V * w.d_t))))   # <= ~2e11 MACs
+        # about 10 s of oracle work on the machine's cores: up to ~6e11 fp64 MACs of whole windows, repeated
+        # when the whole workload is smaller than that
         R = w.K + 1
-        reps = 3 if nwin * R * w.V * w.d_t < 3e10 else 1
+        per_window = R * w.V * w.d_t
+        nwin = min(w.B, max(1, int(6.0e11 // per_window)))
+        reps = max(1, min(64, int(6.0e11 // (nwin * per_window))))
         times = []
         for _ in range(reps):
             t0 = time.perf_counter()
