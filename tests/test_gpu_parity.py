@@ -212,3 +212,74 @@ def test_non_default_stream():
     s.synchronize()
     aj.aj_destroy(h)
     assert np.array_equal(out_len.cpu().numpy(), ref.out_len) and np.array_equal(out_tok.cpu().numpy(), ref.out_tok)
+
+
+def test_maximum_window_length():
+    w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="kmax", B=1, K=1023, d_t=64, d_d=8, V=200, p_match=0.97,
+                  clf_b=-3.0)
+    rep, x, draft, greedy, gpu = parity_case(w, 21, tau=0.5)
+    assert 0 <= gpu["out_len"][0] <= 1023
+
+
+def test_handle_reuse_with_other_inputs_and_two_handles():
+    """A handle keeps no state between calls: results depend on the current arguments only."""
+    import torch
+    import paper_2504_20039_amd as aj
+    w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="reuse", B=3, K=9, d_t=256, d_d=64, V=3000, p_match=0.5)
+    xs = [make_inputs(w, s) for s in (31, 32)]
+    refs, drafts = [], []
+    for x in xs:
+        g = oracle_greedy(x)
+        d = wl.draft_tokens(w, x.seed, g[0])
+        refs.append(oracle.walk(x.ht, x.hd, g[0], d, x.cw, w.clf_b, w.tau))
+        drafts.append(d)
+        assert not oracle.near_tie(g[1], g[2]).any()
+    dev = [[aj.device_tensor(a) for a in (x.ht, x.hd, x.W, d, x.cw)] for x, d in zip(xs, drafts)]
+    h1 = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, aj.AJ_BF16)
+    h2 = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, aj.AJ_BF16)
+    outs = [[torch.zeros(w.B, dtype=torch.int32, device="cuda") for _ in range(2)] for _ in range(4)]
+    # h1: inputs 0, then inputs 1, then inputs 0 again; h2: inputs 1 in between - all enqueued back to back
+    aj.aj_verify(h1, *dev[0], w.clf_b, w.tau, *outs[0])
+    aj.aj_verify(h2, *dev[1], w.clf_b, w.tau, *outs[1])
+    aj.aj_verify(h1, *dev[1], w.clf_b, w.tau, *outs[2])
+    aj.aj_verify(h1, *dev[0], w.clf_b, w.tau, *outs[3])
+    torch.cuda.synchronize()
+    aj.aj_destroy(h1)
+    aj.aj_destroy(h2)
+    for o, r in zip(outs, (refs[0], refs[1], refs[1], refs[0])):
+        assert np.array_equal(o[0].cpu().numpy(), r.out_len) and np.array_equal(o[1].cpu().numpy(), r.out_tok)
+
+
+def test_profile_events_and_kernel_names():
+    import torch
+    import paper_2504_20039_amd as aj
+    w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="prof", B=1, K=16, d_t=4096, d_d=64, V=4096)
+    x = make_inputs(w, 3)
+    dev = [aj.device_tensor(a) for a in (x.ht, x.hd, x.W, np.zeros((w.B, w.K), np.int32), x.cw)]
+    o = [torch.zeros(w.B, dtype=torch.int32, device="cuda") for _ in range(2)]
+    h = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, aj.AJ_BF16, 1, aj.AJ_FLAG_PROFILE)
+    assert aj.aj_kernel_name(h) == "lm_head_stream16_bf16"
+    assert aj.aj_profile_read(h) == []
+    for _ in range(5):
+        aj.aj_verify(h, *dev, 0.0, 0.5, *o)
+    ms = aj.aj_profile_read(h)
+    assert len(ms) == 5 and all(0.0 < t < 50.0 for t in ms)
+    aj.aj_destroy(h)
+    plain = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, aj.AJ_BF16)
+    with pytest.raises(aj.AjError):
+        aj.aj_profile_read(plain)
+    aj.aj_destroy(plain)
+    for M_B, name in ((8, "lm_head_big_bf16"), (4, "lm_head_tile_bf16"), (9, "lm_head_tall_bf16"), (33, "lm_head_tall_bf16")):
+        hh = aj.aj_create(M_B, 31, 4096, 64, 4096, aj.AJ_BF16)     # 256, 128, 288, 1056 verify rows
+        assert aj.aj_kernel_name(hh) == name, (M_B, aj.aj_kernel_name(hh))
+        aj.aj_destroy(hh)
+
+
+@pytest.mark.parametrize("kernel,shape", [
+    (2, dict(B=1, K=16, d_t=4096, d_d=64, V=20000)),
+    (3, dict(B=8, K=31, d_t=512, d_d=64, V=5000)),
+    (4, dict(B=9, K=31, d_t=512, d_d=64, V=5000)),
+])
+def test_run_to_run_bit_identical(kernel, shape):
+    w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="det", p_match=0.5, **shape)
+    parity_case(w, 17, kernel=kernel, repeat=10)
