@@ -49,6 +49,12 @@ bool lm_head_stream16_supports(int M, int V, int d);
 int lm_head_stream16_blocks(int V, int num_cus);
 hipError_t lm_head_stream16_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s);
 
+// 256 x 256 tiles with paired 64-byte half loads (whole 128-byte lines per request pair); d_t % 256 == 0
+bool lm_head_pair_supports(int M, int V, int d);
+int lm_head_pair_blocks(int V);
+int lm_head_pair_padded_rows(int M);
+hipError_t lm_head_pair_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s);
+
 struct TailArgs {
     const void *hidden_t, *hidden_d, *clf_w;
     const int32_t *draft_tok;

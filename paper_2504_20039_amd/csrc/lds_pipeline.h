@@ -49,7 +49,24 @@ __device__ __forceinline__ void wait_vm_lgkm_and_barrier()
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+// Tile order of the persistent kernels: groups of gm row tiles x all column tiles, row tile fastest
+// inside a group, so that consecutive tiles share operand panels.
+struct Sched {
+    int tiles_m, tiles_n, gm, total;
+};
+
+__device__ __forceinline__ void tile_of(const Sched &sc, int T, int &mt, int &nt)
+{
+    const int per_group = sc.gm * sc.tiles_n;
+    const int ngroups = (sc.tiles_m + sc.gm - 1) / sc.gm;
+    int grp = T / per_group;
+    if (grp > ngroups - 1) grp = ngroups - 1;
+    const int within = T - grp * per_group;
+    const int g = (grp == ngroups - 1) ? sc.tiles_m - grp * sc.gm : sc.gm;
+    mt = grp * sc.gm + within % g;
+    nt = within / g;
+}
 
 // grid of a persistent LM-head kernel: one workgroup per CU, a multiple of 8 (the XCD count), and no
 // more workgroups than tiles (rounded up to a multiple of 8 so that the tile -> XCD mapping holds)

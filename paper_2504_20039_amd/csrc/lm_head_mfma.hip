@@ -88,22 +88,6 @@ using BigShape = Shape<4, 4, 2, 2, 1, 32, 4, false, true>;
 using TallShape = Shape<2, 5, 4, 2, 1, 64, 2, false>;                 // 256 x 320, 8 waves: 289..320 verify rows in ONE row tile
 using Tall288Shape = Shape<2, 5, 4, 2, 1, 64, 2, false, false, 1>;   // 256 x 288 (wave rows of 5 + 4 blocks)
 
-struct Sched {
-    int tiles_m, tiles_n, gm, total;
-};
-
-__device__ __forceinline__ void tile_of(const Sched &sc, int T, int &mt, int &nt)
-{
-    const int per_group = sc.gm * sc.tiles_n;
-    const int ngroups = (sc.tiles_m + sc.gm - 1) / sc.gm;
-    int grp = T / per_group;
-    if (grp > ngroups - 1) grp = ngroups - 1;
-    const int within = T - grp * per_group;
-    const int g = (grp == ngroups - 1) ? sc.tiles_m - grp * sc.gm : sc.gm;
-    mt = grp * sc.gm + within % g;
-    nt = within / g;
-}
-
 template <class S, bool DUMP>
 __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched sc)
 {

@@ -9,7 +9,7 @@ from parity import compare, make_inputs, oracle_greedy, parity_case, run_gpu
 pytestmark = pytest.mark.gpu
 
 TINY = wl.WORKLOADS["tiny_f32"]
-KERNELS_BF16 = [1, 2, 3, 4]       # AJ_KERNEL_TILE, _STREAM, _BIG, _TALL (forced); 0 = AUTO is covered too
+KERNELS_BF16 = [1, 2, 3, 4, 5]    # AJ_KERNEL_TILE, _STREAM, _BIG, _TALL, _PAIR (forced); 0 = AUTO is covered too
 
 
 def _skip_unless_supported(w, kernel):
@@ -55,6 +55,7 @@ def test_tiny_f32_workload_with_all_logits():
     dict(B=1, K=16, d_t=4096, d_d=256, V=5003),        # the register-resident streaming kernel, ragged vocabulary
     dict(B=2, K=15, d_t=2048, d_d=128, V=9000),        # ... at d_t = 2048, all 32 rows
     dict(B=1, K=4, d_t=4096, d_d=64, V=40),            # ... fewer tiles than workgroups
+    dict(B=9, K=31, d_t=512, d_d=64, V=60000),         # 2 x 235 large tiles: workgroups with two tiles and with one
 ])
 def test_bf16_shapes_all_kernels(kernel, shape):
     import torch
@@ -269,8 +270,9 @@ def test_profile_events_and_kernel_names():
     with pytest.raises(aj.AjError):
         aj.aj_profile_read(plain)
     aj.aj_destroy(plain)
-    for M_B, name in ((8, "lm_head_big_bf16"), (4, "lm_head_tile_bf16"), (9, "lm_head_tall_bf16"), (33, "lm_head_tall_bf16")):
-        hh = aj.aj_create(M_B, 31, 4096, 64, 4096, aj.AJ_BF16)     # 256, 128, 288, 1056 verify rows
+    for M_B, d_t, name in ((8, 4096, "lm_head_pair_bf16"), (8, 4096 + 64, "lm_head_big_bf16"), (4, 4096, "lm_head_tile_bf16"),
+                           (9, 4096, "lm_head_tall_bf16"), (33, 4096, "lm_head_tall_bf16")):
+        hh = aj.aj_create(M_B, 31, d_t, 64, 4096, aj.AJ_BF16)     # 256, 256, 128, 288, 1056 verify rows
         assert aj.aj_kernel_name(hh) == name, (M_B, aj.aj_kernel_name(hh))
         aj.aj_destroy(hh)
 
@@ -279,6 +281,7 @@ def test_profile_events_and_kernel_names():
     (2, dict(B=1, K=16, d_t=4096, d_d=64, V=20000)),
     (3, dict(B=8, K=31, d_t=512, d_d=64, V=5000)),
     (4, dict(B=9, K=31, d_t=512, d_d=64, V=5000)),
+    (5, dict(B=9, K=31, d_t=768, d_d=64, V=5000)),
 ])
 def test_run_to_run_bit_identical(kernel, shape):
     w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="det", p_match=0.5, **shape)
