@@ -99,19 +99,21 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
         int v = c.kernel;
         if (v == AJ_KERNEL_AUTO) {
             // W_lm-streaming regime while one 32-row block holds every verify row.  From 192 rows on, one
-            // of the two large-tile kernels: 256-row tiles (4 waves, hand-scheduled) or 288/320-row tiles
-            // (8 waves), whichever rounds the row count up less - padded rows are wasted MFMA work, and a
-            // batch of 257..320 rows in ONE row tile also reads W_lm from HBM only once.  At equal padding
-            // the hand-scheduled 256-row kernel is about 4 % faster (measured on the same device), so the
-            // taller tiles must save more rows than that.  Of the two 256-row kernels the one that loads
-            // whole 128-byte lines (d_t a multiple of 256) is about 10 % faster.  The general kernel otherwise.
+            // of the large-tile kernels: 256-row tiles (4 waves, hand-scheduled) or 288/320-row tiles
+            // (8 waves), whichever costs less - padded rows are wasted MFMA work, and a batch of 257..320
+            // rows in ONE row tile also reads W_lm from HBM only once.  Per padded row the 256-row kernel
+            // that loads whole 128-byte lines (d_t a multiple of 256) is about 15 % faster than the 8-wave
+            // kernel and the other 256-row kernel about 4 % (measured on the same device), so the taller
+            // tiles must save more rows than that.  The general kernel otherwise.
             const bool big = h->M >= 192 && lm_head_mfma_supports(AJ_KERNEL_BIG, h->M, c.V, c.d_t);
+            const bool pair = h->M >= 192 && lm_head_pair_supports(h->M, c.V, c.d_t);
             const bool tall = h->M >= 192 && lm_head_mfma_supports(AJ_KERNEL_TALL, h->M, c.V, c.d_t);
+            const double tall_cost = (pair ? 1.15 : 1.04) * lm_head_mfma_padded_rows(AJ_KERNEL_TALL, h->M);
             if (lm_head_stream16_supports(h->M, c.V, c.d_t) ||
                 lm_head_mfma_supports(AJ_KERNEL_STREAM, h->M, c.V, c.d_t)) v = AJ_KERNEL_STREAM;
-            else if (tall && (!big || 1.04 * lm_head_mfma_padded_rows(AJ_KERNEL_TALL, h->M) <
-                                          lm_head_mfma_padded_rows(AJ_KERNEL_BIG, h->M))) v = AJ_KERNEL_TALL;
-            else if (big) v = lm_head_pair_supports(h->M, c.V, c.d_t) ? AJ_KERNEL_PAIR : AJ_KERNEL_BIG;
+            else if (tall && (!(big || pair) || tall_cost < lm_head_pair_padded_rows(h->M))) v = AJ_KERNEL_TALL;
+            else if (pair) v = AJ_KERNEL_PAIR;
+            else if (big) v = AJ_KERNEL_BIG;
             else v = AJ_KERNEL_TILE;
         } else if (v == AJ_KERNEL_PAIR ? (h->M > 0 && !lm_head_pair_supports(h->M, c.V, c.d_t))
                    : v != AJ_KERNEL_TILE && h->M > 0 && !lm_head_mfma_supports(v, h->M, c.V, c.d_t) &&
