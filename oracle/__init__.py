@@ -53,6 +53,12 @@ def _load():
         lib.ajo_walk.restype = i32
         lib.ajo_verify.argtypes = [i32] * 7 + [vp] * 5 + [flt, flt] + [vp] * 10
         lib.ajo_verify.restype = i32
+        lib.ajo_rank_rows.argtypes = [i32, vp, i32, vp, i32, i32] + [vp] * 7
+        lib.ajo_rank_rows.restype = i32
+        lib.ajo_walk_topk.argtypes = [i32, i32, i32, vp, vp, vp, vp]
+        lib.ajo_walk_topk.restype = i32
+        lib.ajo_verify_topk.argtypes = [i32] * 6 + [vp] * 10
+        lib.ajo_verify_topk.restype = i32
         _lib = lib
     return _lib
 
@@ -187,4 +193,71 @@ def verify(hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, feat_offset=1
                             _ptr(r.mismatch), _ptr(r.z), _ptr(r.p), _ptr(r.near_thr))
     if rc:
         raise ValueError(f"ajo_verify rc={rc}")
+    return r
+
+
+# ---- top-K baseline (Section 4: accept a mismatching draft token within the target's top-k tokens)
+
+class RankResult:
+    __slots__ = ("t_star", "max1", "rank", "rank_lo", "rank_hi", "tok_logit")
+
+
+def rank_rows(hidden_t, W_lm, tok) -> RankResult:
+    """Per verify row: the greedy token and the rank of tok[r] (number of vocabulary entries ordered
+    before it: larger logit first, lower index first among equals; -1 = no token, >= V = invalid)."""
+    W_lm = _c(W_lm)
+    V, d_t = W_lm.shape
+    hidden_t = _c(hidden_t).reshape(-1, d_t)
+    tok = _c(tok, np.int32).reshape(-1)
+    M = hidden_t.shape[0]
+    assert tok.shape == (M,) and _code(hidden_t) == _code(W_lm)
+    r = RankResult()
+    r.t_star = np.empty(M, np.int32)
+    r.max1 = np.empty(M, np.float64)
+    r.rank = np.empty(M, np.int32)
+    r.rank_lo = np.empty(M, np.int32)
+    r.rank_hi = np.empty(M, np.int32)
+    r.tok_logit = np.empty(M, np.float64)
+    rc = _load().ajo_rank_rows(_code(W_lm), _ptr(hidden_t), M, _ptr(W_lm), V, d_t, _ptr(tok),
+                               _ptr(r.t_star), _ptr(r.max1), _ptr(r.rank), _ptr(r.rank_lo), _ptr(r.rank_hi),
+                               _ptr(r.tok_logit))
+    if rc:
+        raise ValueError(f"ajo_rank_rows rc={rc}")
+    return r
+
+
+def walk_topk(rank, t_star, top_k: int):
+    """First-reject walk of the baseline: (out_len [B], out_tok [B]) from rank / t_star [B][K+1]."""
+    rank, t_star = _c(rank, np.int32), _c(t_star, np.int32)
+    B, R = rank.shape
+    assert t_star.shape == (B, R)
+    out_len, out_tok = np.empty(B, np.int32), np.empty(B, np.int32)
+    rc = _load().ajo_walk_topk(B, R - 1, int(top_k), _ptr(rank), _ptr(t_star), _ptr(out_len), _ptr(out_tok))
+    if rc:
+        raise ValueError(f"ajo_walk_topk rc={rc}")
+    return out_len, out_tok
+
+
+class TopkResult:
+    __slots__ = ("out_len", "out_tok", "t_star", "max1", "rank", "rank_lo", "rank_hi")
+
+
+def verify_topk(hidden_t, W_lm, draft_tok, top_k: int) -> TopkResult:
+    """The whole top-K baseline step with per-row diagnostics ([B*(K+1)]; the rank entries of the bonus
+    rows are 0)."""
+    draft_tok = _c(draft_tok, np.int32)
+    B, K = draft_tok.shape
+    W_lm = _c(W_lm)
+    V, d_t = W_lm.shape
+    hidden_t = _c(hidden_t).reshape(B, K + 1, d_t)
+    M = B * (K + 1)
+    r = TopkResult()
+    r.out_len, r.out_tok = np.empty(B, np.int32), np.empty(B, np.int32)
+    r.t_star, r.max1 = np.empty(M, np.int32), np.empty(M, np.float64)
+    r.rank, r.rank_lo, r.rank_hi = np.empty(M, np.int32), np.empty(M, np.int32), np.empty(M, np.int32)
+    rc = _load().ajo_verify_topk(B, K, d_t, V, _code(W_lm), int(top_k), _ptr(hidden_t), _ptr(W_lm),
+                                 _ptr(draft_tok), _ptr(r.out_len), _ptr(r.out_tok), _ptr(r.t_star),
+                                 _ptr(r.max1), _ptr(r.rank), _ptr(r.rank_lo), _ptr(r.rank_hi))
+    if rc:
+        raise ValueError(f"ajo_verify_topk rc={rc}")
     return r

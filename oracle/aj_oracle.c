@@ -292,3 +292,152 @@ int ajo_verify(int B, int K, int d_t, int d_d, int V, int dtype, int feat_offset
     free(m2);
     return rc;
 }
+
+/* ------------------------------------------------------------------ top-K baseline (Section 4) */
+
+/*
+ * The simpler lossy baseline of Section 4 ("Our baselines ..."): a mismatching draft token
+ * is accepted when it is among the top_k most likely tokens of the target model.  With the
+ * greedy tie rule extended to an order (larger logit first, lower index first among equals):
+ *
+ *   rank[r] = #{ v : logit[r][v] > logit[r][tok[r]] } + #{ v < tok[r] : logit[r][v] == logit[r][tok[r]] }
+ *
+ * so rank 0 is the greedy token and "within the top_k" is rank < top_k (top_k = 1 is plain
+ * greedy verification, top_k = V accepts every token of the vocabulary).  A token outside
+ * [0,V) is in no top-k: rank = V.
+ *
+ * tok[r] < 0 marks a row without a draft token (the bonus row): rank[r] = 0, nothing counted.
+ * rank_lo / rank_hi (either may be NULL) bracket what a reduced-precision LM head may
+ * count: entries that beat the token by more than band = AJO_NEAR_TIE_REL * |max logit| count in
+ * both, entries within the band of it only in rank_hi.
+ */
+int ajo_rank_rows(int dtype, const void *hidden_t, int M, const void *W_lm, int V, int d_t,
+                  const int32_t *tok, int32_t *t_star, double *max1, int32_t *rank,
+                  int32_t *rank_lo, int32_t *rank_hi, double *tok_logit)
+{
+    if (!hidden_t || !W_lm || !tok || !rank || M < 0 || V <= 0 || d_t <= 0)
+        return -1;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *h = (double *)malloc(sizeof(double) * (size_t)d_t);
+        double *L = (double *)malloc(sizeof(double) * (size_t)V);
+        if (!h || !L) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int r = 0; r < M; ++r) {
+            if (!h || !L)
+                continue;
+            for (int k = 0; k < d_t; ++k)
+                h[k] = widen_at(hidden_t, (size_t)r * (size_t)d_t + (size_t)k, dtype);
+            double best = -INFINITY;
+            int32_t arg = 0;
+            for (int v = 0; v < V; ++v) {
+                L[v] = dot_f64(h, W_lm, (size_t)v * (size_t)d_t, dtype, d_t);
+                if (v == 0 || L[v] > best) {
+                    best = L[v];
+                    arg = v;
+                }
+            }
+            if (t_star) t_star[r] = arg;
+            if (max1) max1[r] = best;
+            const int32_t t = tok[r];
+            int32_t rk = 0, lo = 0, hi = 0;
+            double lt = NAN;
+            if (t >= V) {
+                rk = lo = hi = V;
+            } else if (t >= 0) {
+                lt = L[t];
+                const double band = AJO_NEAR_TIE_REL * fabs(best);
+                for (int v = 0; v < V; ++v) {
+                    if (v == t)
+                        continue;
+                    if (L[v] > lt || (L[v] == lt && v < t)) ++rk;
+                    if (L[v] > lt + band) ++lo;
+                    if (L[v] >= lt - band) ++hi;
+                }
+            }
+            rank[r] = rk;
+            if (rank_lo) rank_lo[r] = lo;
+            if (rank_hi) rank_hi[r] = hi;
+            if (tok_logit) tok_logit[r] = lt;
+        }
+        free(h);
+        free(L);
+    }
+    return fail ? -2 : 0;
+}
+
+/*
+ * First-reject walk of the top-K baseline given rank[B][K+1] (of the draft token of each
+ * slot; the entry of row K is ignored) and the greedy tokens t_star[B][K+1]:
+ * slot j is accepted when rank < top_k; out_len = first rejected slot (K if none),
+ * out_tok = t_star[out_len] as in the judge-augmented walk.
+ */
+int ajo_walk_topk(int B, int K, int top_k, const int32_t *rank, const int32_t *t_star,
+                  int32_t *out_len, int32_t *out_tok)
+{
+    if (B < 0 || K < 1 || top_k < 1 || !rank || !t_star || !out_len || !out_tok)
+        return -1;
+    for (int b = 0; b < B; ++b) {
+        const int32_t *rk = rank + (size_t)b * (size_t)(K + 1);
+        int n = K;
+        for (int j = 0; j < K; ++j) {
+            if (!(rk[j] < top_k)) {
+                n = j;
+                break;
+            }
+        }
+        out_len[b] = n;
+        out_tok[b] = t_star[(size_t)b * (size_t)(K + 1) + (size_t)n];
+    }
+    return 0;
+}
+
+/* The whole baseline step: LM head, ranks of the draft tokens, walk.  Per-row diagnostics
+ * [B*(K+1)] are optional (NULL to skip). */
+int ajo_verify_topk(int B, int K, int d_t, int V, int dtype, int top_k,
+                    const void *hidden_t, const void *W_lm, const int32_t *draft_tok,
+                    int32_t *out_len, int32_t *out_tok,
+                    int32_t *t_star_out, double *max1_out, int32_t *rank_out,
+                    int32_t *rank_lo_out, int32_t *rank_hi_out)
+{
+    if (B < 0 || K < 1 || V <= 0 || top_k < 1)
+        return -1;
+    const int M = B * (K + 1);
+    const size_t n = (size_t)(M > 0 ? M : 1);
+    int32_t *tok = (int32_t *)calloc(n, sizeof(int32_t));
+    int32_t *t = (int32_t *)calloc(n, sizeof(int32_t));
+    int32_t *rk = (int32_t *)calloc(n, sizeof(int32_t));
+    int32_t *lo = (int32_t *)calloc(n, sizeof(int32_t));
+    int32_t *hi = (int32_t *)calloc(n, sizeof(int32_t));
+    double *m1 = (double *)calloc(n, sizeof(double));
+    int rc = -2;
+    if (tok && t && rk && lo && hi && m1) {
+        for (int b = 0; b < B; ++b)
+            for (int j = 0; j <= K; ++j)
+                tok[(size_t)b * (K + 1) + j] = j < K ? draft_tok[(size_t)b * K + j] : -1;
+        for (int r = 0; r < M; ++r)      /* a negative draft token is invalid, not "no token" */
+            if (r % (K + 1) < K && tok[r] < 0) tok[r] = V;
+        rc = M > 0 ? ajo_rank_rows(dtype, hidden_t, M, W_lm, V, d_t, tok, t, m1, rk, lo, hi, NULL) : 0;
+        if (rc == 0)
+            rc = ajo_walk_topk(B, K, top_k, rk, t, out_len, out_tok);
+        if (rc == 0)
+            for (int r = 0; r < M; ++r) {
+                if (t_star_out) t_star_out[r] = t[r];
+                if (max1_out) max1_out[r] = m1[r];
+                if (rank_out) rank_out[r] = rk[r];
+                if (rank_lo_out) rank_lo_out[r] = lo[r];
+                if (rank_hi_out) rank_hi_out[r] = hi[r];
+            }
+    }
+    free(tok);
+    free(t);
+    free(rk);
+    free(lo);
+    free(hi);
+    free(m1);
+    return rc;
+}
