@@ -61,7 +61,8 @@ typedef enum {
 
 enum {
     AJ_FLAG_DEBUG = 1,   /* keep per-slot judge scores for aj_debug_ptrs */
-    AJ_FLAG_PROFILE = 2  /* record HIP events around the LM-head kernel (aj_profile_read) */
+    AJ_FLAG_PROFILE = 2, /* record HIP events around the LM-head kernel (aj_profile_read) */
+    AJ_FLAG_TOPK = 4     /* also allocate the workspace of aj_verify_topk */
 };
 
 /* LM-head kernel choice; AJ_KERNEL_AUTO picks by shape. The others force one for tests/benchmarks. */
@@ -97,6 +98,28 @@ int aj_create(const aj_config *cfg, aj_handle **out);
 int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_d, const void *W_lm,
               const int32_t *draft_tok, const void *clf_w, float clf_b, float tau,
               int32_t *out_len, int32_t *out_tok, void *stream);
+
+/*
+ * The top-K lossy baseline the paper compares against (Section 4, "Our baselines"): a mismatching
+ * draft token is accepted when it is within the top_k most likely tokens of the target model.  Same
+ * LM-head pass as aj_verify; instead of the judge, every logit of a verify row is compared, while still
+ * in registers, with the logit of the row's draft token:
+ *   rank[b][j] = number of vocabulary entries ordered before draft_tok[b][j] in row (b, j)
+ *                (larger logit first, lower index first among equal logits; rank 0 = greedy token);
+ *                V for a token outside [0, V)
+ *   out_len[b] = first slot with rank >= top_k (K if none), out_tok[b] = greedy token of that row.
+ * top_k = 1 is plain greedy verification, top_k >= V accepts every valid token.
+ * Needs AJ_FLAG_TOPK at aj_create (AJ_ESTATE otherwise); AJ_EINVAL on null / misaligned pointers or
+ * top_k < 1.  Arguments as in aj_verify.
+ */
+int aj_verify_topk(aj_handle *h, const void *hidden_t, const void *W_lm, const int32_t *draft_tok,
+                   int32_t top_k, int32_t *out_len, int32_t *out_tok, void *stream);
+
+/*
+ * After aj_verify_topk: rank [B*(K+1)] int32 (0 at the bonus row of each window) copied to a HOST
+ * array; synchronises `stream` first.  t_star / maxlogit of that call are read with aj_debug_copy.
+ */
+int aj_debug_copy_rank(aj_handle *h, int32_t *rank_host, void *stream);
 
 /* Frees the workspace. The caller must have synchronised any stream still using the handle. */
 int aj_destroy(aj_handle *h);

@@ -54,6 +54,7 @@ enum { AJO_F32 = 0, AJO_BF16 = 1 };
 
 #define AJO_NEAR_TIE_REL 1e-3   /* top-2 gap below this times |max| flags the row */
 #define AJO_NEAR_THR_REL 1e-4   /* |z - logit(tau)| below this times max(1,|z|) flags the slot */
+#define AJO_RANK_BAND_REL 1e-4  /* logits closer than this times |max| to a draft token's may count either way */
 
 static inline double widen_at(const void *p, size_t i, int dtype)
 {
@@ -307,9 +308,11 @@ int ajo_verify(int B, int K, int d_t, int d_d, int V, int dtype, int feat_offset
  * [0,V) is in no top-k: rank = V.
  *
  * tok[r] < 0 marks a row without a draft token (the bonus row): rank[r] = 0, nothing counted.
- * rank_lo / rank_hi (either may be NULL) bracket what a reduced-precision LM head may
- * count: entries that beat the token by more than band = AJO_NEAR_TIE_REL * |max logit| count in
- * both, entries within the band of it only in rank_hi.
+ * rank_lo / rank_hi (either may be NULL) bracket what an fp32-accumulating LM head may
+ * count: entries that beat the token by more than band = AJO_RANK_BAND_REL * |max logit| count in
+ * both, entries within the band of it only in rank_hi.  (The band is ~50 x the fp32
+ * accumulation error seen at these sizes, 2e-6 |max logit|; the 1e-3 of the greedy near-tie
+ * rule would span a dozen vocabulary entries for a token in the bulk of the distribution.)
  */
 int ajo_rank_rows(int dtype, const void *hidden_t, int M, const void *W_lm, int V, int d_t,
                   const int32_t *tok, int32_t *t_star, double *max1, int32_t *rank,
@@ -350,7 +353,7 @@ int ajo_rank_rows(int dtype, const void *hidden_t, int M, const void *W_lm, int 
                 rk = lo = hi = V;
             } else if (t >= 0) {
                 lt = L[t];
-                const double band = AJO_NEAR_TIE_REL * fabs(best);
+                const double band = AJO_RANK_BAND_REL * fabs(best);
                 for (int v = 0; v < V; ++v) {
                     if (v == t)
                         continue;

@@ -15,10 +15,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libaj.so")
 
 AJ_F32, AJ_BF16 = 0, 1
-AJ_FLAG_DEBUG, AJ_FLAG_PROFILE = 1, 2
+AJ_FLAG_DEBUG, AJ_FLAG_PROFILE, AJ_FLAG_TOPK = 1, 2, 4
 AJ_KERNEL_AUTO, AJ_KERNEL_TILE, AJ_KERNEL_STREAM, AJ_KERNEL_BIG, AJ_KERNEL_TALL, AJ_KERNEL_PAIR = 0, 1, 2, 3, 4, 5
 
-SYMBOLS = ["aj_create", "aj_verify", "aj_destroy", "aj_debug_ptrs", "aj_debug_copy", "aj_debug_logits",
+SYMBOLS = ["aj_create", "aj_verify", "aj_verify_topk", "aj_debug_copy_rank", "aj_destroy", "aj_debug_ptrs", "aj_debug_copy", "aj_debug_logits",
            "aj_profile_read", "aj_kernel_name", "aj_strerror", "aj_last_hip_error"]
 
 
@@ -57,6 +57,10 @@ def load_library():
     lib.aj_create.restype = ctypes.c_int
     lib.aj_verify.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, vp, vp, vp]
     lib.aj_verify.restype = ctypes.c_int
+    lib.aj_verify_topk.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.aj_verify_topk.restype = ctypes.c_int
+    lib.aj_debug_copy_rank.argtypes = [vp, vp, vp]
+    lib.aj_debug_copy_rank.restype = ctypes.c_int
     lib.aj_destroy.argtypes = [vp]
     lib.aj_destroy.restype = ctypes.c_int
     lib.aj_debug_ptrs.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp)]
@@ -123,6 +127,22 @@ def aj_verify(h, hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, out_len
                                   _stream(stream))
     if rc != 0:
         raise AjError(rc, "aj_verify")
+
+
+def aj_verify_topk(h, hidden_t, W_lm, draft_tok, top_k, out_len, out_tok, stream=None):
+    rc = load_library().aj_verify_topk(h, _ptr(hidden_t), _ptr(W_lm), _ptr(draft_tok), int(top_k),
+                                       _ptr(out_len), _ptr(out_tok), _stream(stream))
+    if rc != 0:
+        raise AjError(rc, "aj_verify_topk")
+
+
+def aj_debug_copy_rank(h, B, K, stream=None):
+    """Host copy of the draft tokens' ranks after aj_verify_topk: int32 [B*(K+1)]."""
+    rank = np.empty(B * (K + 1), np.int32)
+    rc = load_library().aj_debug_copy_rank(h, rank.ctypes.data, _stream(stream))
+    if rc != 0:
+        raise AjError(rc, "aj_debug_copy_rank")
+    return rank
 
 
 def aj_destroy(h):

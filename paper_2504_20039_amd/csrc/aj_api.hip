@@ -19,6 +19,11 @@ struct aj_handle {
     int32_t *t_star;
     float *maxlogit;
     float *score;  // [2][B][K] or nullptr
+    // top-K baseline workspace (AJ_FLAG_TOPK)
+    int32_t *cnt;      // [M][nblocks]
+    float *thr;        // [M]
+    int32_t *thr_tok;  // [M]
+    int32_t *rank;     // [M]
     hipEvent_t ev[64][2];
     bool ev_ok;
     uint64_t calls;
@@ -54,6 +59,10 @@ static void free_all(aj_handle *h)
     if (h->t_star) (void)hipFree(h->t_star);
     if (h->maxlogit) (void)hipFree(h->maxlogit);
     if (h->score) (void)hipFree(h->score);
+    if (h->cnt) (void)hipFree(h->cnt);
+    if (h->thr) (void)hipFree(h->thr);
+    if (h->thr_tok) (void)hipFree(h->thr_tok);
+    if (h->rank) (void)hipFree(h->rank);
     if (h->ev_ok)
         for (int i = 0; i < 64; ++i) {
             (void)hipEventDestroy(h->ev[i][0]);
@@ -135,6 +144,11 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
                   hipMalloc(&h->maxlogit, (size_t)h->M * sizeof(float)) == hipSuccess;
         if (ok && (c.flags & AJ_FLAG_DEBUG))
             ok = hipMalloc(&h->score, (size_t)2 * c.B * c.K * sizeof(float)) == hipSuccess;
+        if (ok && (c.flags & AJ_FLAG_TOPK))
+            ok = hipMalloc(&h->cnt, np * sizeof(int32_t)) == hipSuccess &&
+                 hipMalloc(&h->thr, (size_t)h->M * sizeof(float)) == hipSuccess &&
+                 hipMalloc(&h->thr_tok, (size_t)h->M * sizeof(int32_t)) == hipSuccess &&
+                 hipMalloc(&h->rank, (size_t)h->M * sizeof(int32_t)) == hipSuccess;
         if (!ok) {
             (void)hipGetLastError();
             free_all(h);
@@ -169,7 +183,8 @@ extern "C" int aj_destroy(aj_handle *h)
     return AJ_OK;
 }
 
-static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void *W_lm, float *dump, hipStream_t s)
+static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void *W_lm, float *dump, hipStream_t s,
+                                 bool topk = false)
 {
     LmHeadArgs a;
     a.H = hidden_t;
@@ -180,6 +195,9 @@ static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void 
     a.part = h->part;
     a.nblocks = h->nblocks;
     a.dump = dump;
+    a.thr = topk ? h->thr : nullptr;
+    a.thr_tok = topk ? h->thr_tok : nullptr;
+    a.cnt = topk ? h->cnt : nullptr;
     if (h->variant < 0) return lm_head_f32(a, s);
     if (h->variant == AJ_KERNEL_TILE) return lm_head_tile_bf16(a, s);
     if (h->stream16) return lm_head_stream16_bf16(a, h->num_cus, s);
@@ -234,6 +252,61 @@ extern "C" int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_
     t.out_tok = out_tok;
     if ((e = verify_tail(t, s)) != hipSuccess) return hip_fail(e);
     return AJ_OK;
+}
+
+extern "C" int aj_verify_topk(aj_handle *h, const void *hidden_t, const void *W_lm, const int32_t *draft_tok,
+                              int32_t top_k, int32_t *out_len, int32_t *out_tok, void *stream)
+{
+    if (!h) return AJ_EINVAL;
+    if (top_k < 1) return AJ_EINVAL;
+    if (!(h->cfg.flags & AJ_FLAG_TOPK)) return AJ_ESTATE;
+    if (h->M == 0) return AJ_OK;
+    const aj_config &c = h->cfg;
+    if (!hidden_t || !W_lm || !draft_tok || !out_len || !out_tok) return AJ_EINVAL;
+    if (!aligned16(hidden_t) || !aligned16(W_lm)) return AJ_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+
+    TopkArgs t;
+    t.hidden_t = hidden_t;
+    t.W_lm = W_lm;
+    t.draft_tok = draft_tok;
+    t.B = c.B;
+    t.K = c.K;
+    t.d_t = c.d_t;
+    t.V = c.V;
+    t.dtype = c.dtype;
+    t.top_k = top_k;
+    t.thr = h->thr;
+    t.thr_tok = h->thr_tok;
+    t.part = h->part;
+    t.cnt = h->cnt;
+    t.nblocks = h->nblocks;
+    t.t_star = h->t_star;
+    t.maxlogit = h->maxlogit;
+    t.rank = h->rank;
+    t.out_len = out_len;
+    t.out_tok = out_tok;
+
+    hipError_t e;
+    if ((e = topk_draft_logit(t, s)) != hipSuccess) return hip_fail(e);
+    const bool prof = h->ev_ok;
+    const int slot = (int)(h->calls % 64);
+    if (prof && (e = hipEventRecord(h->ev[slot][0], s)) != hipSuccess) return hip_fail(e);
+    if ((e = launch_lm_head(h, hidden_t, W_lm, nullptr, s, true)) != hipSuccess) return hip_fail(e);
+    if (prof && (e = hipEventRecord(h->ev[slot][1], s)) != hipSuccess) return hip_fail(e);
+    if (prof) h->calls++;
+    if ((e = topk_tail(t, s)) != hipSuccess) return hip_fail(e);
+    return AJ_OK;
+}
+
+extern "C" int aj_debug_copy_rank(aj_handle *h, int32_t *rank_host, void *stream)
+{
+    if (!h || !rank_host) return AJ_EINVAL;
+    if (!(h->cfg.flags & AJ_FLAG_TOPK)) return AJ_ESTATE;
+    if (h->M == 0) return AJ_OK;
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e == hipSuccess) e = hipMemcpy(rank_host, h->rank, (size_t)h->M * sizeof(int32_t), hipMemcpyDeviceToHost);
+    return e == hipSuccess ? AJ_OK : hip_fail(e);
 }
 
 extern "C" int aj_debug_ptrs(aj_handle *h, const int32_t **t_star, const float **maxlogit, const float **score)

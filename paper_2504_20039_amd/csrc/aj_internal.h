@@ -25,11 +25,24 @@ struct LmHeadArgs {
     Best *part;         // [M][nblocks] block maximum and the lowest vocabulary index attaining it
     int nblocks;        // partials per verify row (fixed by the kernel variant and V)
     float *dump;        // debug: all logits [M][V], or nullptr
+    // top-K baseline (all three nullptr otherwise): per verify row the logit and index of its draft
+    // token (+inf and -1 for a row without one), and per (row, block) the number of the block's
+    // vocabulary entries that are ordered before that token
+    const float *thr;       // [M]
+    const int32_t *thr_tok; // [M]
+    int32_t *cnt;           // [M][nblocks]
 };
 
 __device__ __forceinline__ bool better(float v, int32_t i, float bv, int32_t bi)
 {
     return v > bv || (v == bv && i < bi);
+}
+
+// top-K baseline: 1 when vocabulary entry v with logit val is ordered before the row's draft token
+// (logit th, index tk): larger logit first, lower index first among equals; the token itself never.
+__device__ __forceinline__ int32_t ranks_before(float val, int32_t v, float th, int32_t tk)
+{
+    return (int32_t)((v != tk) & ((val > th) | ((val == th) & (v < tk))));
 }
 
 // Number of vocabulary blocks (partials per row) each variant produces for V.
@@ -68,5 +81,24 @@ struct TailArgs {
     int32_t *out_len, *out_tok;
 };
 hipError_t verify_tail(const TailArgs &a, hipStream_t s);     // partials -> t_star; steps 3-4
+
+
+// Top-K baseline: kernels before and after the LM-head pass
+struct TopkArgs {
+    const void *hidden_t, *W_lm;
+    const int32_t *draft_tok;
+    int B, K, d_t, V, dtype, top_k;
+    float *thr;             // [M] out of topk_draft_logit, in of the LM head
+    int32_t *thr_tok;       // [M]
+    const Best *part;       // [M][nblocks]
+    const int32_t *cnt;     // [M][nblocks]
+    int nblocks;
+    int32_t *t_star;        // [M] out
+    float *maxlogit;        // [M] out
+    int32_t *rank;          // [M] out: rank of the slot's draft token (V: not in the vocabulary; 0 for the bonus row)
+    int32_t *out_len, *out_tok;
+};
+hipError_t topk_draft_logit(const TopkArgs &a, hipStream_t s);
+hipError_t topk_tail(const TopkArgs &a, hipStream_t s);
 
 }  // namespace aj

@@ -45,6 +45,9 @@ __global__ __launch_bounds__(256) void k_lm_head_f32(LmHeadArgs a)
         float bv = v < a.V ? acc[i] : -INFINITY;
         int32_t bi = v < a.V ? v : 0x7fffffff;
         if (DUMP && v < a.V && row < a.M) a.dump[(size_t)row * a.V + v] = acc[i];
+        // top-K baseline: is this lane's entry ordered before the row's draft token?
+        int32_t cn = 0;
+        if (a.thr && row < a.M && v < a.V) cn = ranks_before(acc[i], v, a.thr[row], a.thr_tok[row]);
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) {
             float ov = __shfl_xor(bv, off);
@@ -53,9 +56,11 @@ __global__ __launch_bounds__(256) void k_lm_head_f32(LmHeadArgs a)
                 bv = ov;
                 bi = oi;
             }
+            cn += __shfl_xor(cn, off);
         }
         if (lane == 0 && row < a.M) {
             a.part[(size_t)row * a.nblocks + blockIdx.y] = Best{bv, bi};
+            if (a.cnt) a.cnt[(size_t)row * a.nblocks + blockIdx.y] = cn;
         }
     }
 }

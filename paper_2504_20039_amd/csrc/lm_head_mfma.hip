@@ -61,7 +61,7 @@ struct Shape {
     static_assert((BK / 16) % WK == 0, "k steps must split evenly over the k-split waves");
     static_assert((NW * RPI) % 16 == 0, "the chunk a lane fetches must not depend on the load index");
     static_assert((NS - 2) * LPW <= 63, "vmcnt range");
-    static_assert(NS * STAGE_BYTES + BM * WN * 8 + RED_BYTES <= 160 * 1024, "LDS budget");
+    static_assert(NS * STAGE_BYTES + BM * WN * 12 + RED_BYTES <= 160 * 1024, "LDS budget");
     static constexpr int LPP = LPW / KSTEPS;      // PIPE: loads per wave per k step
     // PIPE schedule.  The TN*TM MFMAs of a k step go out in NG groups (x-major order); a "slot" is the
     // shadow of one group.  Fragment reads of the next step (TN + TM of them, in the order fa0, fb0..,
@@ -96,6 +96,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
     constexpr int AHEAD = NS - 1;                  // stages in flight ahead of the one being computed
     __shared__ __attribute__((aligned(1024))) char lds[NS * S::STAGE_BYTES];
     __shared__ Best red[S::BM * (WN > 1 ? WN - 1 : 1)];
+    __shared__ int32_t redc[S::BM * (WN > 1 ? WN - 1 : 1)];     // top-K baseline: counts of the other wave columns
     __shared__ float redk[WK > 1 ? S::RED_BYTES / 4 : 1];
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -153,11 +154,12 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
 
     f32x16 acc[TN][TM];
     float run_v[TM];
-    int32_t run_i[TM];
+    int32_t run_i[TM], run_c[TM];
 #pragma unroll
     for (int y = 0; y < TM; ++y) {
         run_v[y] = -INFINITY;
         run_i[y] = 0x7fffffff;
+        run_c[y] = 0;
     }
 
     // MFMAs of one landed stage (ring buffer `buf`); this wave's share of the k steps
@@ -369,13 +371,20 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
         // ---- greedy maximum: D register r of a lane = vocabulary row 8*(r/4) + 4*(lane/32) + r%4 of its block
         const int v_base = nt * S::BN + wn * TN * 32 + kh * 4;
         float pv[TM];
-        int32_t pi[TM];
+        int32_t pi[TM], pc[TM];
 #pragma unroll
         for (int y = 0; y < TM; ++y) {
             const int lr = wm * TM * 32 + y * 32 + l32;          // verify row inside the tile
             const int row = (y < ty) ? mt * S::BM + lr : a.M;    // a block this wave does not compute: no row
             float bv = S::RUNNING ? run_v[y] : -INFINITY;
             int32_t bi = S::RUNNING ? run_i[y] : 0x7fffffff;
+            // top-K baseline: the row's draft token and the number of this block's entries ordered before it
+            float th = INFINITY;
+            int32_t tk = -1, cn = S::RUNNING ? run_c[y] : 0;
+            if (a.thr && row < a.M) {
+                th = a.thr[row];
+                tk = a.thr_tok[row];
+            }
 #pragma unroll
             for (int x = 0; x < TN; ++x)
 #pragma unroll
@@ -389,22 +398,29 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                             bv = val;
                             bi = v;
                         }
+                        cn += ranks_before(val, v, th, tk);
                     }
                 }
             if (S::RUNNING) {
                 run_v[y] = bv;
                 run_i[y] = bi;
+                run_c[y] = cn;
                 continue;
             }
+            cn += __shfl_xor(cn, 32);
             const float ov = __shfl_xor(bv, 32);
             const int32_t oi = __shfl_xor(bi, 32);
             if (better(ov, oi, bv, bi)) {
                 bv = ov;
                 bi = oi;
             }
-            if (WN > 1 && wn > 0 && kh == 0 && y < ty) red[(wn - 1) * S::BM + lr] = Best{bv, bi};
+            if (WN > 1 && wn > 0 && kh == 0 && y < ty) {
+                red[(wn - 1) * S::BM + lr] = Best{bv, bi};
+                redc[(wn - 1) * S::BM + lr] = cn;
+            }
             pv[y] = bv;
             pi[y] = bi;
+            pc[y] = cn;
         }
         if (!S::RUNNING) {
             // LDS writes of `red` done and visible; do not wait for the prefetch loads in flight
@@ -415,7 +431,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                     const int lr = wm * TM * 32 + y * 32 + l32;
                     const int row = (y < ty) ? mt * S::BM + lr : a.M;
                     float bv = pv[y];
-                    int32_t bi = pi[y];
+                    int32_t bi = pi[y], cn = pc[y];
 #pragma unroll
                     for (int w = 1; w < WN && y < ty; ++w) {
                         const Best o = red[(w - 1) * S::BM + lr];
@@ -423,8 +439,10 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                             bv = o.v;
                             bi = o.i;
                         }
+                        cn += redc[(w - 1) * S::BM + lr];
                     }
                     if (row < a.M) a.part[(size_t)row * a.nblocks + nt] = Best{bv, bi};
+                    if (a.cnt && row < a.M) a.cnt[(size_t)row * a.nblocks + nt] = cn;
                 }
             }
             // `red` is next written after the k-loop barriers of the following tile: no extra barrier
@@ -450,6 +468,10 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
             const int row = y * 32 + l32;
             if (wk == 0 && kh == 0 && row < a.M)
                 a.part[(size_t)row * a.nblocks + blockIdx.x * WN + wn] = Best{bv, bi};
+            if (a.cnt) {
+                const int32_t cn = run_c[y] + __shfl_xor(run_c[y], 32);
+                if (wk == 0 && kh == 0 && row < a.M) a.cnt[(size_t)row * a.nblocks + blockIdx.x * WN + wn] = cn;
+            }
         }
     }
 }

@@ -55,6 +55,7 @@ __global__ __launch_bounds__(256) void k_lm_head_pair(LmHeadArgs a, Sched sc)
     constexpr int TN = 4, TM = 4, NG = 4, GS = 4;
     __shared__ __attribute__((aligned(1024))) char lds[8 * HB];
     __shared__ Best red[PT];
+    __shared__ int32_t redc[PT];      // top-K baseline: counts of the second wave column
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wn = wave & 1, wm = wave >> 1;
@@ -199,13 +200,20 @@ __global__ __launch_bounds__(256) void k_lm_head_pair(LmHeadArgs a, Sched sc)
         // ---- greedy maximum: D register r of a lane = vocabulary row 8*(r/4) + 4*(lane/32) + r%4 of its block
         const int v_base = nt * PT + wn * 128 + kh * 4;
         float pv[TM];
-        int32_t pi[TM];
+        int32_t pi[TM], pc[TM];
 #pragma unroll
         for (int y = 0; y < TM; ++y) {
             const int lr = wm * 128 + y * 32 + l32;          // verify row inside the tile
             const int row = mt * PT + lr;
             float bv = -INFINITY;
             int32_t bi = 0x7fffffff;
+            // top-K baseline: the row's draft token and the number of this block's entries ordered before it
+            float th = INFINITY;
+            int32_t tk = -1, cn = 0;
+            if (a.thr && row < a.M) {
+                th = a.thr[row];
+                tk = a.thr_tok[row];
+            }
 #pragma unroll
             for (int x = 0; x < TN; ++x)
 #pragma unroll
@@ -218,17 +226,23 @@ __global__ __launch_bounds__(256) void k_lm_head_pair(LmHeadArgs a, Sched sc)
                             bv = val;
                             bi = v;
                         }
+                        cn += ranks_before(val, v, th, tk);
                     }
                 }
+            cn += __shfl_xor(cn, 32);
             const float ov = __shfl_xor(bv, 32);
             const int32_t oi = __shfl_xor(bi, 32);
             if (better(ov, oi, bv, bi)) {
                 bv = ov;
                 bi = oi;
             }
-            if (wn > 0 && kh == 0) red[lr] = Best{bv, bi};
+            if (wn > 0 && kh == 0) {
+                red[lr] = Best{bv, bi};
+                redc[lr] = cn;
+            }
             pv[y] = bv;
             pi[y] = bi;
+            pc[y] = cn;
         }
         // LDS writes of `red` done and visible; do not wait for the prefetch loads in flight
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -245,6 +259,7 @@ __global__ __launch_bounds__(256) void k_lm_head_pair(LmHeadArgs a, Sched sc)
                     bi = o.i;
                 }
                 if (row < a.M) a.part[(size_t)row * a.nblocks + nt] = Best{bv, bi};
+                if (a.cnt && row < a.M) a.cnt[(size_t)row * a.nblocks + nt] = pc[y] + redc[lr];
             }
         }
         // `red` is next written after the barriers of the following tile's time steps: no extra barrier

@@ -74,6 +74,19 @@ __global__ __launch_bounds__(S16_WAVES * 64) void k_lm_head_stream16(LmHeadArgs 
 
     float run_v[2] = {-INFINITY, -INFINITY};
     int32_t run_i[2] = {0x7fffffff, 0x7fffffff};
+    // top-K baseline: draft token of this lane's two verify rows and the running count of entries before it
+    float th[2] = {INFINITY, INFINITY};
+    int32_t tk[2] = {-1, -1}, run_c[2] = {0, 0};
+    if (a.thr) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int row = min(b * 16 + l16, a.M - 1);
+            th[b] = a.thr[row];
+            tk[b] = a.thr_tok[row];
+        }
+#pragma unroll
+        for (int b = 0; b < 2; ++b) asm volatile("" : "+v"(th[b]), "+v"(tk[b]));     // retired before the pipeline starts
+    }
 
     int T = tile_at(0);
     if (T < ntiles) {
@@ -129,6 +142,7 @@ __global__ __launch_bounds__(S16_WAVES * 64) void k_lm_head_stream16(LmHeadArgs 
                             run_v[b] = acc[b][r];
                             run_i[b] = v;
                         }
+                        run_c[b] += ranks_before(acc[b][r], v, th[b], tk[b]);
                     }
                 }
         }
@@ -152,6 +166,12 @@ __global__ __launch_bounds__(S16_WAVES * 64) void k_lm_head_stream16(LmHeadArgs 
             }
             const int row = b * 16 + l16;
             if (q4 == 0 && row < a.M) a.part[(size_t)row * a.nblocks + blockIdx.x] = Best{bv, bi};
+            if (a.cnt) {
+                int32_t c = run_c[b];
+                c += __shfl_xor(c, 16);
+                c += __shfl_xor(c, 32);
+                if (q4 == 0 && row < a.M) a.cnt[(size_t)row * a.nblocks + blockIdx.x] = c;
+            }
         }
     }
 }

@@ -27,6 +27,7 @@ __global__ __launch_bounds__(256) void k_lm_head_tile(LmHeadArgs a)
     __shared__ __attribute__((aligned(16))) uint16_t sH[BM * LSTR];
     __shared__ float red_v[BM];
     __shared__ int32_t red_i[BM];
+    __shared__ int32_t red_c[BM];     // top-K baseline: counts of the second wave column
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wv = wave & 1, wh = wave >> 1;     // wave's vocabulary half / verify-row half
@@ -101,6 +102,13 @@ __global__ __launch_bounds__(256) void k_lm_head_tile(LmHeadArgs a)
         const int row = m0 + wh * 64 + y * 32 + i32;
         float bv = -INFINITY;
         int32_t bi = 0x7fffffff;
+        // top-K baseline: the row's draft token and the number of this block's entries ordered before it
+        float th = INFINITY;
+        int32_t tk = -1, cn = 0;
+        if (a.thr && row < a.M) {
+            th = a.thr[row];
+            tk = a.thr_tok[row];
+        }
 #pragma unroll
         for (int x = 0; x < 2; ++x) {
 #pragma unroll
@@ -113,6 +121,7 @@ __global__ __launch_bounds__(256) void k_lm_head_tile(LmHeadArgs a)
                         bv = val;
                         bi = v;
                     }
+                    cn += ranks_before(val, v, th, tk);
                 }
             }
         }
@@ -123,9 +132,11 @@ __global__ __launch_bounds__(256) void k_lm_head_tile(LmHeadArgs a)
             bi = oi;
         }
         const int lr = wh * 64 + y * 32 + i32;
+        cn += __shfl_xor(cn, 32);
         if (wv == 1 && kh == 0) {
             red_v[lr] = bv;
             red_i[lr] = bi;
+            red_c[lr] = cn;
         }
         __syncthreads();
         if (wv == 0 && kh == 0 && row < a.M) {
@@ -134,6 +145,7 @@ __global__ __launch_bounds__(256) void k_lm_head_tile(LmHeadArgs a)
                 bi = red_i[lr];
             }
             a.part[(size_t)row * a.nblocks + blockIdx.y] = Best{bv, bi};
+            if (a.cnt) a.cnt[(size_t)row * a.nblocks + blockIdx.y] = cn + red_c[lr];
         }
         __syncthreads();
     }

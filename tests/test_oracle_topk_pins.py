@@ -155,7 +155,7 @@ def test_rank_brackets_open_only_near_ties():
     H = np.zeros((1, 4), np.float32)
     H[0] = [1, 0, 0, 0]
     W = np.zeros((5, 4), np.float32)
-    W[:, 0] = [4.0, 3.0, 2.0, 2.0 + 1e-4, -1.0]
+    W[:, 0] = [4.0, 3.0, 2.0, 2.0 + 1e-5, -1.0]       # band = 1e-4 * 4
     for tok, rank, lo, hi in ((2, 3, 2, 3), (3, 2, 2, 3), (1, 1, 1, 1), (4, 4, 4, 4)):
         r = oracle.rank_rows(H, W, np.array([tok], np.int32))
         assert (r.rank[0], r.rank_lo[0], r.rank_hi[0]) == (rank, lo, hi), tok
