@@ -40,7 +40,9 @@
  *   - ties of the maximum go to the lowest index, compared as IEEE values.
  *
  * Parity pins (tests/test_oracle_pins.py): every function here is pinned; see
- * that file for the list.
+ * that file for the list.  The top-K baseline of Section 4 (ajo_rank_rows,
+ * ajo_walk_topk, ajo_verify_topk, at the end of this file) is pinned in
+ * tests/test_oracle_topk_pins.py.
  */
 #include <math.h>
 #include <stdint.h>
