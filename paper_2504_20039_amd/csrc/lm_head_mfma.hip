@@ -88,7 +88,7 @@ using BigShape = Shape<4, 4, 2, 2, 1, 32, 4, false, true>;
 using TallShape = Shape<2, 5, 4, 2, 1, 64, 2, false>;                 // 256 x 320, 8 waves: 289..320 verify rows in ONE row tile
 using Tall288Shape = Shape<2, 5, 4, 2, 1, 64, 2, false, false, 1>;   // 256 x 288 (wave rows of 5 + 4 blocks)
 
-template <class S, bool DUMP>
+template <class S, bool DUMP, bool TOPK>
 __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched sc)
 {
     constexpr int TN = S::TN, TM = S::TM, WN = S::WN, WM = S::WM, WK = S::WK, NW = S::NW, BK = S::BK, NS = S::NS;
@@ -127,6 +127,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
     // ring buffer `buf`.  Each load is "uniform 64-bit base + 32-bit lane offset"; the lane offsets are
     // recomputed at every stage (a few VALU ops beside hundreds of MFMA cycles) rather than kept in
     // registers across the k loop - the laundered `rl_now` stops the compiler from hoisting them.
+    const bool w_once = sc.tiles_m == 1;
     auto issue = [&](int mt, int nt, int ks, int buf, int part = -1) {   // part >= 0: only that share of the loads
         int rl_now = rl;
         asm volatile("" : "+v"(rl_now));
@@ -139,7 +140,9 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
             if (part >= 0 && j / S::LPP != part) continue;
             if (j < S::WI / NW) {
                 const int row = min(n_first + j * NW * RPI, a.V - 1);       // clamped: ragged tiles stay in bounds
-                load_to_lds_16(W, __umul24(row, rowbytes) + koff, stage + j * NW * 1024);
+                // with a single row tile W_lm is streamed from HBM exactly once: non-temporal
+                if (w_once) load_to_lds_16_nt(W, __umul24(row, rowbytes) + koff, stage + j * NW * 1024);
+                else load_to_lds_16(W, __umul24(row, rowbytes) + koff, stage + j * NW * 1024);
             } else {
                 // H load jj of this wave is tile load jj*NW + wave; a wave that has none left (HI is not a
                 // multiple of NW) repeats its previous one: same rows to the same place, harmless
@@ -381,7 +384,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
             // top-K baseline: the row's draft token and the number of this block's entries ordered before it
             float th = INFINITY;
             int32_t tk = -1, cn = S::RUNNING ? run_c[y] : 0;
-            if (a.thr && row < a.M) {
+            if (TOPK && row < a.M) {
                 th = a.thr[row];
                 tk = a.thr_tok[row];
             }
@@ -398,7 +401,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                             bv = val;
                             bi = v;
                         }
-                        cn += ranks_before(val, v, th, tk);
+                        if (TOPK) cn += ranks_before(val, v, th, tk);
                     }
                 }
             if (S::RUNNING) {
@@ -407,7 +410,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                 run_c[y] = cn;
                 continue;
             }
-            cn += __shfl_xor(cn, 32);
+            if (TOPK) cn += __shfl_xor(cn, 32);
             const float ov = __shfl_xor(bv, 32);
             const int32_t oi = __shfl_xor(bi, 32);
             if (better(ov, oi, bv, bi)) {
@@ -416,7 +419,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
             }
             if (WN > 1 && wn > 0 && kh == 0 && y < ty) {
                 red[(wn - 1) * S::BM + lr] = Best{bv, bi};
-                redc[(wn - 1) * S::BM + lr] = cn;
+                if (TOPK) redc[(wn - 1) * S::BM + lr] = cn;
             }
             pv[y] = bv;
             pi[y] = bi;
@@ -439,10 +442,10 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                             bv = o.v;
                             bi = o.i;
                         }
-                        cn += redc[(w - 1) * S::BM + lr];
+                        if (TOPK) cn += redc[(w - 1) * S::BM + lr];
                     }
                     if (row < a.M) a.part[(size_t)row * a.nblocks + nt] = Best{bv, bi};
-                    if (a.cnt && row < a.M) a.cnt[(size_t)row * a.nblocks + nt] = cn;
+                    if (TOPK && row < a.M) a.cnt[(size_t)row * a.nblocks + nt] = cn;
                 }
             }
             // `red` is next written after the k-loop barriers of the following tile: no extra barrier
@@ -468,7 +471,7 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
             const int row = y * 32 + l32;
             if (wk == 0 && kh == 0 && row < a.M)
                 a.part[(size_t)row * a.nblocks + blockIdx.x * WN + wn] = Best{bv, bi};
-            if (a.cnt) {
+            if (TOPK) {
                 const int32_t cn = run_c[y] + __shfl_xor(run_c[y], 32);
                 if (wk == 0 && kh == 0 && row < a.M) a.cnt[(size_t)row * a.nblocks + blockIdx.x * WN + wn] = cn;
             }
@@ -485,10 +488,13 @@ hipError_t launch(const LmHeadArgs &a, int num_cus, int gm, hipStream_t s)
     sc.gm = gm < 1 ? 1 : (gm > sc.tiles_m ? sc.tiles_m : gm);
     sc.total = sc.tiles_m * sc.tiles_n;
     const int grid = persistent_grid(num_cus, sc.total);
+    // the top-K baseline's counting is a separate instantiation: the judge path pays nothing for it
     if (a.dump)
-        hipLaunchKernelGGL((k_lm_head_mfma<S, true>), dim3(grid), dim3(S::NW * 64), 0, s, a, sc);
+        hipLaunchKernelGGL((k_lm_head_mfma<S, true, false>), dim3(grid), dim3(S::NW * 64), 0, s, a, sc);
+    else if (a.thr)
+        hipLaunchKernelGGL((k_lm_head_mfma<S, false, true>), dim3(grid), dim3(S::NW * 64), 0, s, a, sc);
     else
-        hipLaunchKernelGGL((k_lm_head_mfma<S, false>), dim3(grid), dim3(S::NW * 64), 0, s, a, sc);
+        hipLaunchKernelGGL((k_lm_head_mfma<S, false, false>), dim3(grid), dim3(S::NW * 64), 0, s, a, sc);
     return hipGetLastError();
 }
 

@@ -49,7 +49,7 @@ constexpr int buf_h(int u)
 template <int U>
 using step_c = std::integral_constant<int, U>;
 
-template <bool DUMP>
+template <bool DUMP, bool TOPK>
 __global__ __launch_bounds__(256) void k_lm_head_pair(LmHeadArgs a, Sched sc)
 {
     constexpr int TN = 4, TM = 4, NG = 4, GS = 4;
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(256) void k_lm_head_pair(LmHeadArgs a, Sched sc)
             // top-K baseline: the row's draft token and the number of this block's entries ordered before it
             float th = INFINITY;
             int32_t tk = -1, cn = 0;
-            if (a.thr && row < a.M) {
+            if (TOPK && row < a.M) {
                 th = a.thr[row];
                 tk = a.thr_tok[row];
             }
@@ -226,10 +226,10 @@ __global__ __launch_bounds__(256) void k_lm_head_pair(LmHeadArgs a, Sched sc)
                             bv = val;
                             bi = v;
                         }
-                        cn += ranks_before(val, v, th, tk);
+                        if (TOPK) cn += ranks_before(val, v, th, tk);
                     }
                 }
-            cn += __shfl_xor(cn, 32);
+            if (TOPK) cn += __shfl_xor(cn, 32);
             const float ov = __shfl_xor(bv, 32);
             const int32_t oi = __shfl_xor(bi, 32);
             if (better(ov, oi, bv, bi)) {
@@ -238,7 +238,7 @@ __global__ __launch_bounds__(256) void k_lm_head_pair(LmHeadArgs a, Sched sc)
             }
             if (wn > 0 && kh == 0) {
                 red[lr] = Best{bv, bi};
-                redc[lr] = cn;
+                if (TOPK) redc[lr] = cn;
             }
             pv[y] = bv;
             pi[y] = bi;
@@ -259,7 +259,7 @@ __global__ __launch_bounds__(256) void k_lm_head_pair(LmHeadArgs a, Sched sc)
                     bi = o.i;
                 }
                 if (row < a.M) a.part[(size_t)row * a.nblocks + nt] = Best{bv, bi};
-                if (a.cnt && row < a.M) a.cnt[(size_t)row * a.nblocks + nt] = pc[y] + redc[lr];
+                if (TOPK && row < a.M) a.cnt[(size_t)row * a.nblocks + nt] = pc[y] + redc[lr];
             }
         }
         // `red` is next written after the barriers of the following tile's time steps: no extra barrier
@@ -299,8 +299,10 @@ hipError_t lm_head_pair_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s)
     sc.gm = sc.tiles_m < 8 ? sc.tiles_m : 8;
     sc.total = sc.tiles_m * sc.tiles_n;
     const int grid = persistent_grid(num_cus, sc.total);
-    if (a.dump) hipLaunchKernelGGL((k_lm_head_pair<true>), dim3(grid), dim3(256), 0, s, a, sc);
-    else hipLaunchKernelGGL((k_lm_head_pair<false>), dim3(grid), dim3(256), 0, s, a, sc);
+    // the top-K baseline's counting is a separate instantiation: the judge path pays nothing for it
+    if (a.dump) hipLaunchKernelGGL((k_lm_head_pair<true, false>), dim3(grid), dim3(256), 0, s, a, sc);
+    else if (a.thr) hipLaunchKernelGGL((k_lm_head_pair<false, true>), dim3(grid), dim3(256), 0, s, a, sc);
+    else hipLaunchKernelGGL((k_lm_head_pair<false, false>), dim3(grid), dim3(256), 0, s, a, sc);
     return hipGetLastError();
 }
 
