@@ -1,20 +1,24 @@
 // LM head (step 1) + running greedy maximum (first half of step 2) for the W_lm-streaming regime:
 // at most 32 verify rows, d_t = 2048 or 4096.  HBM-bound: the only operand that moves is W_lm.
 //
-//   * hidden_t lives in REGISTERS for the whole kernel.  The 8 waves of a workgroup split the k range
-//     of every stage; a wave keeps the v_mfma_f32_16x16x32_bf16 B-fragments (column = verify row) of
-//     its own k sub-ranges: d_t/256 stages x 2 row blocks x 4 VGPRs = 128 VGPRs at d_t = 4096.
-//   * tiles of 16 vocabulary rows; a stage is 16 rows x 512 bytes = 8 KB, one direct-to-LDS load per
-//     wave; d_t/256 (= 16) stages in the ring, i.e. 120 KB of W_lm in flight per compute unit.  Few
-//     rows with long contiguous runs in flight is what the HBM likes best: on this chip a load-only
-//     kernel with this very pattern reads at 6.55 TB/s, with 32-row tiles at 6.1, with 128 rows x
-//     256 B at 5.0.
-//   * the ring has as many stages as a tile has k stages, so stage ks always sits in buffer ks and
-//     every LDS address in the unrolled loop is a compile-time constant.
-//   * per tile the 8 partial 16x32 logit blocks are added through LDS by wave 0, which keeps a
-//     running (max, lowest index) per lane; one partial per verify row and workgroup is written at
-//     the end.  Lane l of the MFMA result holds verify row l % 16 and vocabulary rows 4*(l/16)+r:
-//     ascending inside a lane and over a workgroup's tiles, so strict > keeps the lowest index.
+//   * hidden_t lives in REGISTERS for the whole kernel.  The 8 waves of a workgroup split the k range:
+//     wave w owns k in [w*d_t/8, (w+1)*d_t/8) and keeps the v_mfma_f32_16x16x32_bf16 B-fragments
+//     (column = verify row) of that range: d_t/256 k steps x 2 row blocks x 4 VGPRs = 128 VGPRs at
+//     d_t = 4096.
+//   * tiles of 16 vocabulary rows.  Every wave streams ITS OWN k slice of the tile - 16 rows x 512 B per
+//     stage, eight 1 KB direct-to-LDS loads of two whole 512-byte row segments each - through a private
+//     two-buffer ring, so the load pipeline needs no workgroup barrier: a wave issues its next stage,
+//     waits for its own loads of the current one (s_waitcnt vmcnt), and computes it (8 fragment reads,
+//     16 MFMAs).  One stage per wave, 64 KB per compute unit, is always in flight.  Few rows with long
+//     contiguous runs is what the HBM likes best: load-only kernels with this pattern read 6.9 TB/s on
+//     this chip, with 32-row tiles 6.7, with 128 rows x 256 B 5.0.
+//   * W_lm is read exactly once, so its loads carry the non-temporal hint (6.2 -> 6.5 TB/s).
+//   * per tile the 8 partial 16x32 logit blocks meet in LDS and every wave adds up one eighth of the block
+//     (one accumulator register index: verify rows 16b..16b+15 x vocabulary rows 4q+r for its (b, r)),
+//     keeping a running (max, lowest index) per lane: no wave does more than the others, and the two
+//     barriers of this exchange are the only ones of a tile.  Lane l holds verify row l % 16 and
+//     vocabulary row 4*(l/16) + r of the tile: ascending over a workgroup's tiles, so strict > keeps the
+//     lowest index; the 4 waves of a row block are merged once, at the end.
 #include "../../include/aj.h"
 #include "aj_internal.h"
 #include "lds_pipeline.h"
@@ -24,170 +28,177 @@ namespace aj {
 namespace {
 
 constexpr int S16_WAVES = 8;
-constexpr int S16_ROWS = 16;                 // vocabulary rows per tile
-constexpr int S16_SEG = 512;                 // bytes of each row per stage (256 k elements, 32 per wave)
-constexpr int S16_STAGE = S16_ROWS * S16_SEG;  // 8 KB = one 1 KB load per wave
+constexpr int S16_ROWS = 16;                    // vocabulary rows per tile
+constexpr int S16_SEG = 512;                    // bytes of each row per stage (256 k elements = 8 k steps)
+constexpr int S16_STAGE = S16_ROWS * S16_SEG;   // 8 KB = eight 1 KB loads
+constexpr int S16_LOADS = S16_STAGE / 1024;
 
-template <int KS, bool DUMP, bool TOPK>   // d_t = KS * 256; ring of KS stages
+template <int NST, bool DUMP, bool TOPK>   // NST stages per tile and wave: d_t = NST * 2048
 __global__ __launch_bounds__(S16_WAVES * 64) void k_lm_head_stream16(LmHeadArgs a, int ntiles)
 {
-    constexpr int NS = KS, AHEAD = NS - 1;
-    __shared__ __attribute__((aligned(1024))) char lds[NS * S16_STAGE];
-    __shared__ float redk[(S16_WAVES - 1) * 8 * 64];
+    constexpr int KSTEPS = 8;                   // k steps of 32 per stage
+    __shared__ __attribute__((aligned(1024))) char lds[S16_WAVES * 2 * S16_STAGE];   // per wave: 2 stage buffers
+    __shared__ float redk[S16_WAVES * 8 * 64];  // partial logit blocks: [source wave][register][lane]
+    __shared__ Best fin[32 * 4];                // final merge of the 4 waves of a row block
+    __shared__ int32_t finc[32 * 4];
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l16 = lane & 15, q4 = lane >> 4;
     const char *W = (const char *)a.W, *H = (const char *)a.H;
     const uint32_t rowbytes = (uint32_t)a.d * 2u;
-    const uint32_t lds_base = lds_offset_of(lds);
+    const uint32_t kslice = (uint32_t)wave * (NST * S16_SEG);      // byte offset of this wave's k range in a row
+    const uint32_t lds_mine = lds_offset_of(lds) + wave * (2 * S16_STAGE);
+    const char *lds_rd = lds + wave * (2 * S16_STAGE);
 
     // persistent tile list: runs of (gridDim/8) consecutive tiles per XCD
     const int G = gridDim.x, xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, SL = G >> 3;
     auto tile_at = [&](int step) { return (step * 8 + xcd) * SL + slot; };
 
-    // loader: this wave's load covers tile rows 2*wave, 2*wave+1; lane i fills slot (row i/32, chunk i%32)
-    // and fetches global chunk (i%32) ^ row (XOR swizzle on the low 4 bits: conflict-free fragment reads)
-    const int tr = 2 * wave + (lane >> 5);
-    const uint32_t cg16 = (uint32_t)(((lane & 31) ^ tr) * 16);
-    auto issue = [&](int tile, int ks) {          // stage ks of `tile` into buffer ks
-        const int row = min(tile * S16_ROWS + tr, a.V - 1);
-        lds_dma_16_nt(W, __umul24(row, rowbytes) + (uint32_t)(ks * S16_SEG) + cg16,     // W_lm is read exactly once
-                   lds_base + ks * S16_STAGE + wave * 1024);
+    // loader: load j of a stage covers tile rows 2j, 2j+1; lane i fills slot (row i/32, chunk i%32) and
+    // fetches global chunk (i%32) ^ row (XOR on the low 4 bits: conflict-free fragment reads)
+    const int rsub = lane >> 5;
+    auto issue = [&](int tile, int st, int buf) {    // stage st of `tile` (this wave's k slice) into buffer buf
+        const uint32_t dst = lds_mine + buf * S16_STAGE;
+        const uint32_t koff = kslice + (uint32_t)(st * S16_SEG);
+#pragma unroll
+        for (int j = 0; j < S16_LOADS; ++j) {
+            const int tr = 2 * j + rsub;
+            const int row = min(tile * S16_ROWS + tr, a.V - 1);    // clamped: a ragged last tile stays in bounds
+            lds_dma_16_nt(W, __umul24(row, rowbytes) + koff + (uint32_t)(((lane & 31) ^ tr) * 16), dst + j * 1024);
+        }
     };
-    // A fragment (16 vocabulary rows x 32 k): lane (row l16, k group q4) reads chunk 4*wave + q4 of its row
-    const int a_off = l16 * S16_SEG + (((4 * wave + q4) ^ l16) * 16);
+    // A fragment (16 vocabulary rows x 32 k) of k step t: lane (row l16, k group q4) reads chunk 4t + q4
+    const int a_base = l16 * S16_SEG;
 
-    // hidden_t fragments: block b = verify rows 16b..16b+15 (clamped), k = ks*256 + wave*32 + q4*8 ..+8
-    bf16x8 hf[KS][2];
+    // hidden_t fragments of this wave's k range: block b = verify rows 16b..16b+15 (clamped)
+    bf16x8 hf[NST * KSTEPS][2];
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
-        const char *hrow = H + (size_t)min(b * 16 + l16, a.M - 1) * rowbytes;
+        const char *hrow = H + (size_t)min(b * 16 + l16, a.M - 1) * rowbytes + kslice;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) hf[ks][b] = *(const bf16x8 *)(hrow + (ks * 256 + wave * 32 + q4 * 8) * 2);
+        for (int t = 0; t < NST * KSTEPS; ++t) hf[t][b] = *(const bf16x8 *)(hrow + (t * 32 + q4 * 8) * 2);
+    }
+    // this wave's share of every tile: accumulator register (bsel, rsel); its verify row and, for the
+    // top-K baseline, that row's draft token
+    const int bsel = wave >> 2, rsel = wave & 3;
+    const int myrow = bsel * 16 + l16;
+    float th = INFINITY;
+    int32_t tk = -1, run_c = 0;
+    if (TOPK) {
+        th = a.thr[min(myrow, a.M - 1)];
+        tk = a.thr_tok[min(myrow, a.M - 1)];
     }
     // make the compiler retire these loads here: its waits must not land inside the pipelined loop,
     // where they would drain the kernel's own asynchronous loads
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(hf[ks][b]));
+        for (int t = 0; t < NST * KSTEPS; ++t) asm volatile("" : "+v"(hf[t][b]));
+    asm volatile("" : "+v"(th), "+v"(tk));
 
-    float run_v[2] = {-INFINITY, -INFINITY};
-    int32_t run_i[2] = {0x7fffffff, 0x7fffffff};
-    // top-K baseline: draft token of this lane's two verify rows and the running count of entries before it
-    float th[2] = {INFINITY, INFINITY};
-    int32_t tk[2] = {-1, -1}, run_c[2] = {0, 0};
-    if (TOPK) {
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int row = min(b * 16 + l16, a.M - 1);
-            th[b] = a.thr[row];
-            tk[b] = a.thr_tok[row];
-        }
-#pragma unroll
-        for (int b = 0; b < 2; ++b) asm volatile("" : "+v"(th[b]), "+v"(tk[b]));     // retired before the pipeline starts
-    }
+    float run_v = -INFINITY;
+    int32_t run_i = 0x7fffffff;
 
+    // Stages of this wave are numbered f = step * NST + st and use buffer f & 1.  At stage f the wave first
+    // issues stage f+1 into the other buffer (its fragments went to registers during stage f-1), then
+    // waits until only those loads are outstanding - loads complete in order - and computes stage f.
     int T = tile_at(0);
-    if (T < ntiles) {
-#pragma unroll
-        for (int p = 0; p < AHEAD; ++p) issue(T, p);
-    }
+    if (T < ntiles) issue(T, 0, 0);
     for (int step = 0; T < ntiles; ++step) {
         const int T2 = tile_at(step + 1);
         const bool have_next = T2 < ntiles;
         f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            // stage ks has landed once at most the NS-2 younger loads of this wave are outstanding; the
-            // barrier also frees buffer ks-1 (computed in the previous iteration) for the load issued
-            // now.  Without a next tile fewer loads are in flight: wait for all.
-            if (ks == 0) {
-                wait_vm_and_barrier<NS - 2>();
-                issue(T, AHEAD);                       // last stage of this tile into buffer NS-1
+        for (int st = 0; st < NST; ++st) {
+            const int cur = NST == 2 ? st : (step & 1);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the other buffer's fragment reads are done
+            if (st + 1 < NST) {
+                issue(T, st + 1, cur ^ 1);
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(S16_LOADS) : "memory");
             } else if (have_next) {
-                wait_vm_and_barrier<NS - 2>();
-                issue(T2, ks - 1);
+                issue(T2, 0, cur ^ 1);
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(S16_LOADS) : "memory");
             } else {
-                wait_vm_and_barrier<0>();
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             }
-            const bf16x8 fa = *(const bf16x8 *)(lds + ks * S16_STAGE + a_off);
-            acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, hf[ks][0], acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, hf[ks][1], acc[1], 0, 0, 0);
+            const char *buf = lds_rd + cur * S16_STAGE;
+#pragma unroll
+            for (int t = 0; t < KSTEPS; ++t) {
+                const bf16x8 fa = *(const bf16x8 *)(buf + a_base + (((4 * t + q4) ^ l16) * 16));
+                acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, hf[st * KSTEPS + t][0], acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, hf[st * KSTEPS + t][1], acc[1], 0, 0, 0);
+            }
         }
 
-        // add the 8 waves' partial sums (wave 0 collects)
-        if (wave > 0) {
+        // ---- the 8 partial blocks meet in LDS; wave w adds up register (bsel, rsel) of all of them
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) redk[(((wave - 1) * 2 + b) * 4 + r) * 64 + lane] = acc[b][r];
-        }
+            for (int r = 0; r < 4; ++r) redk[((wave * 2 + b) * 4 + r) * 64 + lane] = acc[b][r];
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        if (wave == 0) {
+        float sum = 0.f;
 #pragma unroll
-            for (int w = 1; w < S16_WAVES; ++w)
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[b][r] += redk[(((w - 1) * 2 + b) * 4 + r) * 64 + lane];
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int v = T * S16_ROWS + q4 * 4 + r;
-                    if (v < a.V) {
-                        if (DUMP && b * 16 + l16 < a.M) a.dump[(size_t)(b * 16 + l16) * a.V + v] = acc[b][r];
-                        if (acc[b][r] > run_v[b]) {
-                            run_v[b] = acc[b][r];
-                            run_i[b] = v;
-                        }
-                        if (TOPK) run_c[b] += ranks_before(acc[b][r], v, th[b], tk[b]);
-                    }
-                }
+        for (int w = 0; w < S16_WAVES; ++w) sum += redk[((w * 2 + bsel) * 4 + rsel) * 64 + lane];
+        // everyone has read before anyone writes the next tile's partials
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        const int v = T * S16_ROWS + q4 * 4 + rsel;
+        if (v < a.V) {
+            if (DUMP && myrow < a.M) a.dump[(size_t)myrow * a.V + v] = sum;
+            if (sum > run_v) {
+                run_v = sum;
+                run_i = v;
+            }
+            if (TOPK) run_c += ranks_before(sum, v, th, tk);
         }
-        // redk is rewritten only after the KS stage barriers of the next tile
         T = T2;
     }
 
-    if (wave == 0) {
+    // ---- merge: the 4 vocabulary sub-rows of a lane group, then the 4 waves of a row block
+    float bv = run_v;
+    int32_t bi = run_i, cn = run_c;
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            float bv = run_v[b];
-            int32_t bi = run_i[b];
-#pragma unroll
-            for (int off = 16; off <= 32; off <<= 1) {
-                const float ov = __shfl_xor(bv, off);
-                const int32_t oi = __shfl_xor(bi, off);
-                if (better(ov, oi, bv, bi)) {
-                    bv = ov;
-                    bi = oi;
-                }
-            }
-            const int row = b * 16 + l16;
-            if (q4 == 0 && row < a.M) a.part[(size_t)row * a.nblocks + blockIdx.x] = Best{bv, bi};
-            if (TOPK) {
-                int32_t c = run_c[b];
-                c += __shfl_xor(c, 16);
-                c += __shfl_xor(c, 32);
-                if (q4 == 0 && row < a.M) a.cnt[(size_t)row * a.nblocks + blockIdx.x] = c;
-            }
+    for (int off = 16; off <= 32; off <<= 1) {
+        const float ov = __shfl_xor(bv, off);
+        const int32_t oi = __shfl_xor(bi, off);
+        if (better(ov, oi, bv, bi)) {
+            bv = ov;
+            bi = oi;
         }
+        cn += __shfl_xor(cn, off);
+    }
+    if (q4 == 0) {
+        fin[myrow * 4 + rsel] = Best{bv, bi};
+        finc[myrow * 4 + rsel] = cn;
+    }
+    __syncthreads();
+    if (rsel == 0 && q4 == 0 && myrow < a.M) {
+        cn = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const Best o = fin[myrow * 4 + r];
+            if (r == 0 || better(o.v, o.i, bv, bi)) {
+                bv = o.v;
+                bi = o.i;
+            }
+            cn += finc[myrow * 4 + r];
+        }
+        a.part[(size_t)myrow * a.nblocks + blockIdx.x] = Best{bv, bi};
+        if (TOPK) a.cnt[(size_t)myrow * a.nblocks + blockIdx.x] = cn;
     }
 }
 
-template <int KS>
+template <int NST>
 hipError_t launch16(const LmHeadArgs &a, int num_cus, hipStream_t s)
 {
     const int ntiles = (a.V + S16_ROWS - 1) / S16_ROWS;
     const int grid = persistent_grid(num_cus, ntiles);
     // the top-K baseline's counting is a separate instantiation: the judge path pays nothing for it
     if (a.dump)
-        hipLaunchKernelGGL((k_lm_head_stream16<KS, true, false>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
+        hipLaunchKernelGGL((k_lm_head_stream16<NST, true, false>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
     else if (a.thr)
-        hipLaunchKernelGGL((k_lm_head_stream16<KS, false, true>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
+        hipLaunchKernelGGL((k_lm_head_stream16<NST, false, true>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
     else
-        hipLaunchKernelGGL((k_lm_head_stream16<KS, false, false>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
+        hipLaunchKernelGGL((k_lm_head_stream16<NST, false, false>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
     return hipGetLastError();
 }
 
@@ -205,7 +216,7 @@ int lm_head_stream16_blocks(int V, int num_cus) { return persistent_grid(num_cus
 hipError_t lm_head_stream16_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s)
 {
     if (a.M <= 0) return hipSuccess;
-    return a.d == 4096 ? launch16<16>(a, num_cus, s) : launch16<8>(a, num_cus, s);
+    return a.d == 4096 ? launch16<2>(a, num_cus, s) : launch16<1>(a, num_cus, s);
 }
 
 }  // namespace aj
