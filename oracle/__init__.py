@@ -59,6 +59,12 @@ def _load():
         lib.ajo_walk_topk.restype = i32
         lib.ajo_verify_topk.argtypes = [i32] * 6 + [vp] * 10
         lib.ajo_verify_topk.restype = i32
+        lib.ajo_gumbel.argtypes = [ctypes.c_uint64, i32]
+        lib.ajo_gumbel.restype = dbl
+        lib.ajo_sampled_rows.argtypes = [i32, vp, i32, vp, i32, i32, dbl, vp, vp, vp, vp]
+        lib.ajo_sampled_rows.restype = i32
+        lib.ajo_verify_sampled.argtypes = [i32] * 7 + [vp] * 5 + [flt, flt, flt, vp] + [vp] * 10
+        lib.ajo_verify_sampled.restype = i32
         _lib = lib
     return _lib
 
@@ -260,4 +266,56 @@ def verify_topk(hidden_t, W_lm, draft_tok, top_k: int) -> TopkResult:
                                  _ptr(r.max1), _ptr(r.rank), _ptr(r.rank_lo), _ptr(r.rank_hi))
     if rc:
         raise ValueError(f"ajo_verify_topk rc={rc}")
+    return r
+
+
+# ---- sampling mode (Appendix A: Gumbel-max reparameterisation of stochastic decoding)
+
+def gumbel(key: int, v: int) -> float:
+    """Standard Gumbel noise of vocabulary entry v under a row key (the counter-based generator of the oracle)."""
+    return float(_load().ajo_gumbel(int(key) & 0xFFFFFFFFFFFFFFFF, int(v)))
+
+
+def sampled_rows(hidden_t, W_lm, inv_temperature: float, row_key):
+    """(y int32 [M], max1 f64 [M], max2 f64 [M]): argmax of logit / T + Gumbel(key, v) per verify row."""
+    W_lm = _c(W_lm)
+    V, d_t = W_lm.shape
+    hidden_t = _c(hidden_t).reshape(-1, d_t)
+    M = hidden_t.shape[0]
+    row_key = _c(row_key, np.uint64).reshape(-1)
+    assert row_key.shape == (M,) and _code(hidden_t) == _code(W_lm)
+    y, m1, m2 = np.empty(M, np.int32), np.empty(M, np.float64), np.empty(M, np.float64)
+    rc = _load().ajo_sampled_rows(_code(W_lm), _ptr(hidden_t), M, _ptr(W_lm), V, d_t, float(inv_temperature),
+                                  _ptr(row_key), _ptr(y), _ptr(m1), _ptr(m2))
+    if rc:
+        raise ValueError(f"ajo_sampled_rows rc={rc}")
+    return y, m1, m2
+
+
+def verify_sampled(hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, inv_temperature, row_key,
+                   feat_offset=1) -> VerifyResult:
+    """The whole step with the target's tokens sampled (t_star holds the sampled tokens, max1/max2 the
+    perturbed scores)."""
+    draft_tok = _c(draft_tok, np.int32)
+    B, K = draft_tok.shape
+    W_lm, clf_w = _c(W_lm), _c(clf_w)
+    V, d_t = W_lm.shape
+    d_d = clf_w.shape[0] - d_t
+    hidden_t = _c(hidden_t).reshape(B, K + 1, d_t)
+    hidden_d = _c(hidden_d).reshape(B, K + 1, d_d) if d_d > 0 else None
+    row_key = _c(row_key, np.uint64).reshape(B, K + 1)
+    M = B * (K + 1)
+    r = VerifyResult()
+    r.out_len, r.out_tok = np.empty(B, np.int32), np.empty(B, np.int32)
+    r.t_star, r.max1, r.max2 = np.empty(M, np.int32), np.empty(M, np.float64), np.empty(M, np.float64)
+    r.near_tie = np.empty(M, np.uint8)
+    r.mismatch, r.near_thr = np.empty((B, K), np.uint8), np.empty((B, K), np.uint8)
+    r.z, r.p = np.empty((B, K), np.float64), np.empty((B, K), np.float64)
+    rc = _load().ajo_verify_sampled(B, K, d_t, d_d, V, _code(W_lm), feat_offset,
+                                    _ptr(hidden_t), _ptr(hidden_d), _ptr(W_lm), _ptr(draft_tok), _ptr(clf_w),
+                                    float(clf_b), float(tau), float(inv_temperature), _ptr(row_key),
+                                    _ptr(r.out_len), _ptr(r.out_tok), _ptr(r.t_star), _ptr(r.max1), _ptr(r.max2),
+                                    _ptr(r.near_tie), _ptr(r.mismatch), _ptr(r.z), _ptr(r.p), _ptr(r.near_thr))
+    if rc:
+        raise ValueError(f"ajo_verify_sampled rc={rc}")
     return r

@@ -42,7 +42,8 @@
  * Parity pins (tests/test_oracle_pins.py): every function here is pinned; see
  * that file for the list.  The top-K baseline of Section 4 (ajo_rank_rows,
  * ajo_walk_topk, ajo_verify_topk, at the end of this file) is pinned in
- * tests/test_oracle_topk_pins.py.
+ * tests/test_oracle_topk_pins.py, the sampling mode of Appendix A (ajo_gumbel,
+ * ajo_sampled_rows, ajo_verify_sampled) in tests/test_oracle_sampling_pins.py.
  */
 #include <math.h>
 #include <stdint.h>
@@ -444,5 +445,129 @@ int ajo_verify_topk(int B, int K, int d_t, int V, int dtype, int top_k,
     free(lo);
     free(hi);
     free(m1);
+    return rc;
+}
+
+/* ------------------------------------------------------------------ sampling mode (Appendix A) */
+
+/*
+ * Stochastic decoding as a deterministic function of a random state (Appendix A, "Generalization
+ * to sampling"): the target's token of a verify row is
+ *
+ *     y[r] = argmax_v ( logit[r][v] / T + G(key[r], v) ),     G = standard Gumbel noise,
+ *
+ * which is distributed as softmax(logit[r] / T) (Gumbel-max trick) and reproducible given the
+ * key - in the paper the key stands for the random state joined with the row's context; here
+ * the caller supplies one 64-bit key per verify row.  Everything after the token (mismatch test,
+ * judge, first-reject walk) is the greedy pipeline with y in place of the greedy token.
+ *
+ * The paper names no generator.  This one is counter-based so that every (row, v) can be
+ * evaluated independently, and is specified by this text, which the GPU library implements
+ * on its own:
+ *     h = v * 0x9E3779B1 + lo32(key);  h ^= h >> 16;  h *= 0x85EBCA6B;  h ^= h >> 13;
+ *     h += hi32(key);  h *= 0xC2B2AE35;  h ^= h >> 16;               (all mod 2^32)
+ *     u = ((h >> 8) + 0.5) * 2^-24   in (0,1);      G = -log(-log(u))
+ * u is exact in fp32 and fp64; the oracle takes the logarithms in fp64.
+ */
+static inline uint32_t ajo_noise_bits(uint64_t key, uint32_t v)
+{
+    uint32_t h = v * 0x9E3779B1u + (uint32_t)(key & 0xffffffffu);
+    h ^= h >> 16;
+    h *= 0x85EBCA6Bu;
+    h ^= h >> 13;
+    h += (uint32_t)(key >> 32);
+    h *= 0xC2B2AE35u;
+    h ^= h >> 16;
+    return h;
+}
+
+double ajo_gumbel(uint64_t key, int32_t v)
+{
+    const double u = ((double)(ajo_noise_bits(key, (uint32_t)v) >> 8) + 0.5) * (1.0 / 16777216.0);
+    return -log(-log(u));
+}
+
+/*
+ * Sampled token of each of M verify rows: y[r] = lowest v attaining the maximum of the perturbed
+ * scores; max1 / max2 = largest and second-largest perturbed score (as in ajo_greedy_rows).
+ */
+int ajo_sampled_rows(int dtype, const void *hidden_t, int M, const void *W_lm, int V, int d_t,
+                     double inv_temperature, const uint64_t *row_key,
+                     int32_t *y, double *max1, double *max2)
+{
+    if (!hidden_t || !W_lm || !y || !row_key || M < 0 || V <= 0 || d_t <= 0 || !(inv_temperature >= 0.0))
+        return -1;
+    int fail = 0;
+#pragma omp parallel
+    {
+        double *h = (double *)malloc(sizeof(double) * (size_t)d_t);
+        if (!h) {
+#pragma omp atomic write
+            fail = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (int r = 0; r < M; ++r) {
+            if (!h)
+                continue;
+            for (int k = 0; k < d_t; ++k)
+                h[k] = widen_at(hidden_t, (size_t)r * (size_t)d_t + (size_t)k, dtype);
+            double best = -INFINITY, second = -INFINITY;
+            int32_t arg = 0;
+            for (int v = 0; v < V; ++v) {
+                const double s = dot_f64(h, W_lm, (size_t)v * (size_t)d_t, dtype, d_t) * inv_temperature
+                                 + ajo_gumbel(row_key[r], v);
+                if (v == 0) {
+                    best = s;
+                    arg = 0;
+                } else if (s > best) {
+                    second = best;
+                    best = s;
+                    arg = v;
+                } else if (s > second) {
+                    second = s;
+                }
+            }
+            y[r] = arg;
+            if (max1) max1[r] = best;
+            if (max2) max2[r] = second;
+        }
+        free(h);
+    }
+    return fail ? -2 : 0;
+}
+
+/* The whole step in sampling mode; arguments as ajo_verify plus the temperature and the keys. */
+int ajo_verify_sampled(int B, int K, int d_t, int d_d, int V, int dtype, int feat_offset,
+                       const void *hidden_t, const void *hidden_d, const void *W_lm,
+                       const int32_t *draft_tok, const void *clf_w, float clf_b, float tau,
+                       float inv_temperature, const uint64_t *row_key,
+                       int32_t *out_len, int32_t *out_tok,
+                       int32_t *y_out, double *max1_out, double *max2_out, uint8_t *near_tie,
+                       uint8_t *mismatch, double *z_out, double *p_out, uint8_t *near_thr)
+{
+    if (B < 0 || K < 1 || V <= 0)
+        return -1;
+    int M = B * (K + 1);
+    int32_t *t = (int32_t *)calloc((size_t)(M > 0 ? M : 1), sizeof(int32_t));
+    double *m1 = (double *)calloc((size_t)(M > 0 ? M : 1), sizeof(double));
+    double *m2 = (double *)calloc((size_t)(M > 0 ? M : 1), sizeof(double));
+    int rc = -2;
+    if (t && m1 && m2) {
+        rc = M > 0 ? ajo_sampled_rows(dtype, hidden_t, M, W_lm, V, d_t, (double)inv_temperature, row_key, t, m1, m2) : 0;
+        if (rc == 0)
+            rc = ajo_walk(B, K, d_t, d_d, dtype, feat_offset, hidden_t, hidden_d, t, draft_tok,
+                          clf_w, clf_b, tau, out_len, out_tok, mismatch, z_out, p_out, near_thr);
+        if (rc == 0) {
+            for (int r = 0; r < M; ++r) {
+                if (y_out) y_out[r] = t[r];
+                if (max1_out) max1_out[r] = m1[r];
+                if (max2_out) max2_out[r] = m2[r];
+                if (near_tie) near_tie[r] = (uint8_t)((m1[r] - m2[r]) < AJO_NEAR_TIE_REL * fabs(m1[r]));
+            }
+        }
+    }
+    free(t);
+    free(m1);
+    free(m2);
     return rc;
 }
