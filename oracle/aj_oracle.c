@@ -466,8 +466,9 @@ int ajo_verify_topk(int B, int K, int d_t, int V, int dtype, int top_k,
  * on its own:
  *     h = v * 0x9E3779B1 + lo32(key);  h ^= h >> 16;  h *= 0x85EBCA6B;  h ^= h >> 13;
  *     h += hi32(key);  h *= 0xC2B2AE35;  h ^= h >> 16;               (all mod 2^32)
- *     u = ((h >> 8) + 0.5) * 2^-24   in (0,1);      G = -log(-log(u))
- * u is exact in fp32 and fp64; the oracle takes the logarithms in fp64.
+ *     u = ((h >> 9) + 0.5) * 2^-23   in (0,1);      G = -log(-log(u))
+ * 23 bits, so that u (an odd multiple of 2^-24 below 1) is exact in fp32 as well as in fp64; the
+ * oracle takes the logarithms in fp64.
  */
 static inline uint32_t ajo_noise_bits(uint64_t key, uint32_t v)
 {
@@ -483,7 +484,7 @@ static inline uint32_t ajo_noise_bits(uint64_t key, uint32_t v)
 
 double ajo_gumbel(uint64_t key, int32_t v)
 {
-    const double u = ((double)(ajo_noise_bits(key, (uint32_t)v) >> 8) + 0.5) * (1.0 / 16777216.0);
+    const double u = ((double)(ajo_noise_bits(key, (uint32_t)v) >> 9) + 0.5) * (1.0 / 8388608.0);
     return -log(-log(u));
 }
 
