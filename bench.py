@@ -36,9 +36,11 @@ def main():
     ap.add_argument("--workload", default="8b_b1_k16")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--kernel", type=int, default=0)
-    ap.add_argument("--mode", choices=["judge", "topk"], default="judge",
-                    help="judge: the judge-augmented step (the metric); topk: the paper's top-K lossy baseline "
-                         "on the same LM-head pass")
+    ap.add_argument("--mode", choices=["judge", "topk", "sample"], default="judge",
+                    help="judge: the judge-augmented step with greedy target tokens (the metric); topk: the paper's "
+                         "top-K lossy baseline on the same LM-head pass; sample: the judge-augmented step with "
+                         "Gumbel-max sampled target tokens")
+    ap.add_argument("--inv-temperature", type=float, default=1.0)
     ap.add_argument("--top-k", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -75,13 +77,22 @@ def main():
     out_len = torch.zeros(w.B, dtype=torch.int32, device="cuda")
     out_tok = torch.zeros(w.B, dtype=torch.int32, device="cuda")
     topk = args.mode == "topk"
+    sample = args.mode == "sample"
+    d_key = None
+    if sample:
+        keys = np.random.default_rng(seed).integers(0, 2**63, size=(w.B, w.K + 1), dtype=np.int64)
+        d_key = torch.from_numpy(keys).cuda()
     extra = aj.AJ_FLAG_TOPK if topk else 0
     h = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, w.dtype_code, 1, extra, args.kernel)
     hp = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, w.dtype_code, 1, aj.AJ_FLAG_PROFILE | extra, args.kernel)
     # draft tokens follow the workload recipe relative to the target's greedy tokens; those come
     # from a first (untimed) call of the library itself, with a placeholder draft
     d_draft = torch.zeros((w.B, w.K), dtype=torch.int32, device="cuda")
-    aj.aj_verify(h, d_ht, d_hd, d_W, d_draft, d_cw, w.clf_b, w.tau, out_len, out_tok)
+    if sample:
+        aj.aj_verify_sampled(h, d_ht, d_hd, d_W, d_draft, d_cw, w.clf_b, w.tau, args.inv_temperature, d_key,
+                             out_len, out_tok)
+    else:
+        aj.aj_verify(h, d_ht, d_hd, d_W, d_draft, d_cw, w.clf_b, w.tau, out_len, out_tok)
     torch.cuda.synchronize()
     t_star, _, _ = aj.aj_debug_copy(h, w.B, w.K, want_score=False)
     draft = wl.draft_tokens(w, seed, t_star)
@@ -90,6 +101,9 @@ def main():
     def step(handle):
         if topk:
             aj.aj_verify_topk(handle, d_ht, d_W, d_draft, args.top_k, out_len, out_tok)
+        elif sample:
+            aj.aj_verify_sampled(handle, d_ht, d_hd, d_W, d_draft, d_cw, w.clf_b, w.tau, args.inv_temperature,
+                                 d_key, out_len, out_tok)
         else:
             aj.aj_verify(handle, d_ht, d_hd, d_W, d_draft, d_cw, w.clf_b, w.tau, out_len, out_tok)
 
@@ -135,7 +149,8 @@ def main():
                 hbm_gbs=byts / (k1_ms * 1e-3) / 1e9, mfma_tflops=flops / (k1_ms * 1e-3) / 1e12)
 
     result = {
-        "metric": "verified spec windows/sec (LM-head+argmax+judge) at 1 GPU" if not topk else
+        "metric": "verified spec windows/sec (LM-head+Gumbel-max sample+judge) at 1 GPU" if sample else
+                  "verified spec windows/sec (LM-head+argmax+judge) at 1 GPU" if not topk else
                   "verified spec windows/sec (LM-head+argmax+top-K baseline) at 1 GPU",
         "value": w.B / (ms_per_step * 1e-3),
         "unit": "windows/s",
@@ -145,7 +160,8 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "K": w.K, "d_t": w.d_t, "d_d": w.d_d, "V": w.V,
                    "verify_rows": w.M, "tau": w.tau, "p_match": w.p_match, "seed": seed,
-                   **({"mode": "topk", "top_k": args.top_k} if topk else {})},
+                   **({"mode": "topk", "top_k": args.top_k} if topk else {}),
+                   **({"mode": "sample", "inv_temperature": args.inv_temperature} if sample else {})},
         "verify_rows_per_s": w.M / (ms_per_step * 1e-3),
         "emitted_tokens_per_s": float((accepted + 1).sum()) / (ms_per_step * 1e-3),
         "mean_accepted_len": float(accepted.mean()),
@@ -166,6 +182,9 @@ def main():
             t0 = time.perf_counter()
             if topk:
                 ref = oracle.verify_topk(ht[:nwin * R], W, draft[:nwin], args.top_k)
+            elif sample:
+                ref = oracle.verify_sampled(ht[:nwin * R], hd[:nwin * R], W, draft[:nwin], cw, w.clf_b, w.tau,
+                                            args.inv_temperature, keys[:nwin].view(np.uint64))
             else:
                 ref = oracle.verify(ht[:nwin * R], hd[:nwin * R], W, draft[:nwin], cw, w.clf_b, w.tau)
             times.append(time.perf_counter() - t0)

@@ -100,6 +100,27 @@ int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_d, const vo
               int32_t *out_len, int32_t *out_tok, void *stream);
 
 /*
+ * The same steps for stochastic decoding, made a deterministic function of a random state with the
+ * Gumbel-max trick (Appendix A, "Generalization to sampling"): the target's token of a verify row is
+ *     y[r] = lowest v attaining max_v ( logit[r][v] * inv_temperature + G(row_key[r], v) )
+ * with G standard Gumbel noise, so that y[r] is distributed as softmax(logit[r] / T); the mismatch test,
+ * the judge and the scan then run on y as they do on the greedy token in aj_verify.
+ *   row_key [B][K+1] uint64  device; one key per verify row - what the caller's random state joined with
+ *                            the row's context hashes to (the same key gives the same noise)
+ *   inv_temperature          1/T >= 0, finite (0: uniformly random tokens; large: greedy decoding)
+ * Noise generator (counter-based, any (row, v) on its own), all arithmetic mod 2^32:
+ *     h = v * 0x9E3779B1 + lo32(key); h ^= h >> 16; h *= 0x85EBCA6B; h ^= h >> 13;
+ *     h += hi32(key); h *= 0xC2B2AE35; h ^= h >> 16;
+ *     u = ((h >> 9) + 0.5) * 2^-23;   G = -log(-log(u))
+ * aj_debug_* then report y and the perturbed maximum in place of the greedy token and its logit.
+ * Errors as aj_verify, plus AJ_EINVAL for a null or misaligned row_key or a bad inv_temperature.
+ */
+int aj_verify_sampled(aj_handle *h, const void *hidden_t, const void *hidden_d, const void *W_lm,
+                      const int32_t *draft_tok, const void *clf_w, float clf_b, float tau,
+                      float inv_temperature, const uint64_t *row_key,
+                      int32_t *out_len, int32_t *out_tok, void *stream);
+
+/*
  * The top-K lossy baseline the paper compares against (Section 4, "Our baselines"): a mismatching
  * draft token is accepted when it is within the top_k most likely tokens of the target model.  Same
  * LM-head pass as aj_verify; instead of the judge, every logit of a verify row is compared, while still

@@ -184,7 +184,7 @@ extern "C" int aj_destroy(aj_handle *h)
 }
 
 static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void *W_lm, float *dump, hipStream_t s,
-                                 bool topk = false)
+                                 bool topk = false, const uint64_t *key = nullptr, float inv_temp = 1.f)
 {
     LmHeadArgs a;
     a.H = hidden_t;
@@ -198,6 +198,8 @@ static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void 
     a.thr = topk ? h->thr : nullptr;
     a.thr_tok = topk ? h->thr_tok : nullptr;
     a.cnt = topk ? h->cnt : nullptr;
+    a.key = key;
+    a.inv_temp = inv_temp;
     if (h->variant < 0) return lm_head_f32(a, s);
     if (h->variant == AJ_KERNEL_TILE) return lm_head_tile_bf16(a, s);
     if (h->stream16) return lm_head_stream16_bf16(a, h->num_cus, s);
@@ -205,9 +207,10 @@ static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void 
     return lm_head_mfma_bf16(h->variant, a, h->num_cus, s);
 }
 
-extern "C" int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_d, const void *W_lm,
+// aj_verify and aj_verify_sampled: the same steps; key == nullptr selects the greedy token
+static int verify_common(aj_handle *h, const void *hidden_t, const void *hidden_d, const void *W_lm,
                          const int32_t *draft_tok, const void *clf_w, float clf_b, float tau,
-                         int32_t *out_len, int32_t *out_tok, void *stream)
+                         const uint64_t *key, float inv_temp, int32_t *out_len, int32_t *out_tok, void *stream)
 {
     if (!h) return AJ_EINVAL;
     if (!(tau >= 0.f && tau <= 1.f)) return AJ_EINVAL;   // also refuses NaN
@@ -224,7 +227,7 @@ extern "C" int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_
     const int slot = (int)(h->calls % 64);
     hipError_t e;
     if (prof && (e = hipEventRecord(h->ev[slot][0], s)) != hipSuccess) return hip_fail(e);
-    if ((e = launch_lm_head(h, hidden_t, W_lm, nullptr, s)) != hipSuccess) return hip_fail(e);
+    if ((e = launch_lm_head(h, hidden_t, W_lm, nullptr, s, false, key, inv_temp)) != hipSuccess) return hip_fail(e);
     if (prof && (e = hipEventRecord(h->ev[slot][1], s)) != hipSuccess) return hip_fail(e);
     if (prof) h->calls++;
 
@@ -252,6 +255,26 @@ extern "C" int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_
     t.out_tok = out_tok;
     if ((e = verify_tail(t, s)) != hipSuccess) return hip_fail(e);
     return AJ_OK;
+}
+
+extern "C" int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_d, const void *W_lm,
+                         const int32_t *draft_tok, const void *clf_w, float clf_b, float tau,
+                         int32_t *out_len, int32_t *out_tok, void *stream)
+{
+    return verify_common(h, hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, nullptr, 1.f, out_len, out_tok,
+                         stream);
+}
+
+extern "C" int aj_verify_sampled(aj_handle *h, const void *hidden_t, const void *hidden_d, const void *W_lm,
+                                 const int32_t *draft_tok, const void *clf_w, float clf_b, float tau,
+                                 float inv_temperature, const uint64_t *row_key,
+                                 int32_t *out_len, int32_t *out_tok, void *stream)
+{
+    if (!h) return AJ_EINVAL;
+    if (!(inv_temperature >= 0.f) || !isfinite(inv_temperature)) return AJ_EINVAL;
+    if (h->M > 0 && (!row_key || (((uintptr_t)row_key) & 7u))) return AJ_EINVAL;
+    return verify_common(h, hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, row_key, inv_temperature, out_len,
+                         out_tok, stream);
 }
 
 extern "C" int aj_verify_topk(aj_handle *h, const void *hidden_t, const void *W_lm, const int32_t *draft_tok,

@@ -31,6 +31,10 @@ struct LmHeadArgs {
     const float *thr;       // [M]
     const int32_t *thr_tok; // [M]
     int32_t *cnt;           // [M][nblocks]
+    // sampling mode (nullptr otherwise): one 64-bit key per verify row; the kernels maximise
+    // logit * inv_temp + Gumbel noise(key, vocabulary index) instead of the logit
+    const uint64_t *key;    // [M]
+    float inv_temp;
 };
 
 __device__ __forceinline__ bool better(float v, int32_t i, float bv, int32_t bi)
@@ -43,6 +47,25 @@ __device__ __forceinline__ bool better(float v, int32_t i, float bv, int32_t bi)
 __device__ __forceinline__ int32_t ranks_before(float val, int32_t v, float th, int32_t tk)
 {
     return (int32_t)((v != tk) & ((val > th) | ((val == th) & (v < tk))));
+}
+
+// Sampling mode (Appendix A, "Generalization to sampling": argmax of log-probabilities plus Gumbel noise
+// from a generator seeded by the random state and the context).  Counter-based generator, one 64-bit key
+// per verify row:  h = v * 0x9E3779B1 + lo32(key); h ^= h >> 16; h *= 0x85EBCA6B; h ^= h >> 13;
+// h += hi32(key); h *= 0xC2B2AE35; h ^= h >> 16;  u = ((h >> 9) + 0.5) * 2^-23 (exact in fp32);
+// noise = -log(-log(u)).  Both logarithms are the accurate ones: the largest noise values, which decide
+// the maximum, come from u within 1e-4 of 1, where a fast log2 has no relative accuracy.
+__device__ __forceinline__ float gumbel_noise(uint32_t klo, uint32_t khi, uint32_t v)
+{
+    uint32_t h = v * 0x9E3779B1u + klo;
+    h ^= h >> 16;
+    h *= 0x85EBCA6Bu;
+    h ^= h >> 13;
+    h += khi;
+    h *= 0xC2B2AE35u;
+    h ^= h >> 16;
+    const float u = ((float)(h >> 9) + 0.5f) * (1.0f / 8388608.0f);
+    return -logf(-logf(u));
 }
 
 // Number of vocabulary blocks (partials per row) each variant produces for V.

@@ -42,9 +42,13 @@ __global__ __launch_bounds__(256) void k_lm_head_f32(LmHeadArgs a)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int row = m0 + wave * 4 + i;
+        if (DUMP && v < a.V && row < a.M) a.dump[(size_t)row * a.V + v] = acc[i];
+        if (a.key && row < a.M && v < a.V) {     // sampling mode: logit / T + Gumbel noise(row key, v)
+            const uint64_t key = a.key[row];
+            acc[i] = fmaf(acc[i], a.inv_temp, gumbel_noise((uint32_t)key, (uint32_t)(key >> 32), (uint32_t)v));
+        }
         float bv = v < a.V ? acc[i] : -INFINITY;
         int32_t bi = v < a.V ? v : 0x7fffffff;
-        if (DUMP && v < a.V && row < a.M) a.dump[(size_t)row * a.V + v] = acc[i];
         // top-K baseline: is this lane's entry ordered before the row's draft token?
         int32_t cn = 0;
         if (a.thr && row < a.M && v < a.V) cn = ranks_before(acc[i], v, a.thr[row], a.thr_tok[row]);

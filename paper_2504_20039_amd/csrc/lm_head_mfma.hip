@@ -88,7 +88,7 @@ using BigShape = Shape<4, 4, 2, 2, 1, 32, 4, false, true>;
 using TallShape = Shape<2, 5, 4, 2, 1, 64, 2, false>;                 // 256 x 320, 8 waves: 289..320 verify rows in ONE row tile
 using Tall288Shape = Shape<2, 5, 4, 2, 1, 64, 2, false, false, 1>;   // 256 x 288 (wave rows of 5 + 4 blocks)
 
-template <class S, bool DUMP, bool TOPK>
+template <class S, bool DUMP, bool TOPK, bool SAMPLE>
 __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched sc)
 {
     constexpr int TN = S::TN, TM = S::TM, WN = S::WN, WM = S::WM, WK = S::WK, NW = S::NW, BK = S::BK, NS = S::NS;
@@ -388,14 +388,20 @@ __global__ __launch_bounds__(S::NW * 64) void k_lm_head_mfma(LmHeadArgs a, Sched
                 th = a.thr[row];
                 tk = a.thr_tok[row];
             }
+            uint32_t klo = 0, khi = 0;      // sampling mode: the row's noise key
+            if (SAMPLE && row < a.M) {
+                klo = (uint32_t)a.key[row];
+                khi = (uint32_t)(a.key[row] >> 32);
+            }
 #pragma unroll
             for (int x = 0; x < TN; ++x)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int v = v_base + x * 32 + (r >> 2) * 8 + (r & 3);
-                    const float val = acc[x][y][r];
+                    float val = acc[x][y][r];
                     if (v < a.V) {
                         if (DUMP && row < a.M && wk == 0) a.dump[(size_t)row * a.V + v] = val;
+                        if (SAMPLE) val = fmaf(val, a.inv_temp, gumbel_noise(klo, khi, (uint32_t)v));
                         // ascending v inside a lane and over a workgroup's tiles: strict > keeps the lowest
                         if (val > bv) {
                             bv = val;
@@ -488,13 +494,16 @@ hipError_t launch(const LmHeadArgs &a, int num_cus, int gm, hipStream_t s)
     sc.gm = gm < 1 ? 1 : (gm > sc.tiles_m ? sc.tiles_m : gm);
     sc.total = sc.tiles_m * sc.tiles_n;
     const int grid = persistent_grid(num_cus, sc.total);
-    // the top-K baseline's counting is a separate instantiation: the judge path pays nothing for it
+    // the top-K baseline's counting and the sampling noise are separate instantiations: the greedy judge path
+    // pays nothing for them
     if (a.dump)
-        hipLaunchKernelGGL((k_lm_head_mfma<S, true, false>), dim3(grid), dim3(S::NW * 64), 0, s, a, sc);
+        hipLaunchKernelGGL((k_lm_head_mfma<S, true, false, false>), dim3(grid), dim3(S::NW * 64), 0, s, a, sc);
     else if (a.thr)
-        hipLaunchKernelGGL((k_lm_head_mfma<S, false, true>), dim3(grid), dim3(S::NW * 64), 0, s, a, sc);
+        hipLaunchKernelGGL((k_lm_head_mfma<S, false, true, false>), dim3(grid), dim3(S::NW * 64), 0, s, a, sc);
+    else if (a.key)
+        hipLaunchKernelGGL((k_lm_head_mfma<S, false, false, true>), dim3(grid), dim3(S::NW * 64), 0, s, a, sc);
     else
-        hipLaunchKernelGGL((k_lm_head_mfma<S, false, false>), dim3(grid), dim3(S::NW * 64), 0, s, a, sc);
+        hipLaunchKernelGGL((k_lm_head_mfma<S, false, false, false>), dim3(grid), dim3(S::NW * 64), 0, s, a, sc);
     return hipGetLastError();
 }
 

@@ -49,7 +49,7 @@ constexpr int buf_h(int u)
 template <int U>
 using step_c = std::integral_constant<int, U>;
 
-template <bool DUMP, bool TOPK>
+template <bool DUMP, bool TOPK, bool SAMPLE>
 __global__ __launch_bounds__(256) void k_lm_head_pair(LmHeadArgs a, Sched sc)
 {
     constexpr int TN = 4, TM = 4, NG = 4, GS = 4;
@@ -214,14 +214,20 @@ __global__ __launch_bounds__(256) void k_lm_head_pair(LmHeadArgs a, Sched sc)
                 th = a.thr[row];
                 tk = a.thr_tok[row];
             }
+            uint32_t klo = 0, khi = 0;      // sampling mode: the row's noise key
+            if (SAMPLE && row < a.M) {
+                klo = (uint32_t)a.key[row];
+                khi = (uint32_t)(a.key[row] >> 32);
+            }
 #pragma unroll
             for (int x = 0; x < TN; ++x)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int v = v_base + x * 32 + (r >> 2) * 8 + (r & 3);
-                    const float val = acc[x][y][r];
+                    float val = acc[x][y][r];
                     if (v < a.V) {
                         if (DUMP && row < a.M) a.dump[(size_t)row * a.V + v] = val;
+                        if (SAMPLE) val = fmaf(val, a.inv_temp, gumbel_noise(klo, khi, (uint32_t)v));
                         if (val > bv) {      // ascending v inside a lane: strict > keeps the lowest index
                             bv = val;
                             bi = v;
@@ -299,10 +305,12 @@ hipError_t lm_head_pair_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s)
     sc.gm = sc.tiles_m < 8 ? sc.tiles_m : 8;
     sc.total = sc.tiles_m * sc.tiles_n;
     const int grid = persistent_grid(num_cus, sc.total);
-    // the top-K baseline's counting is a separate instantiation: the judge path pays nothing for it
-    if (a.dump) hipLaunchKernelGGL((k_lm_head_pair<true, false>), dim3(grid), dim3(256), 0, s, a, sc);
-    else if (a.thr) hipLaunchKernelGGL((k_lm_head_pair<false, true>), dim3(grid), dim3(256), 0, s, a, sc);
-    else hipLaunchKernelGGL((k_lm_head_pair<false, false>), dim3(grid), dim3(256), 0, s, a, sc);
+    // the top-K baseline's counting and the sampling noise are separate instantiations: the greedy judge path
+    // pays nothing for them
+    if (a.dump) hipLaunchKernelGGL((k_lm_head_pair<true, false, false>), dim3(grid), dim3(256), 0, s, a, sc);
+    else if (a.thr) hipLaunchKernelGGL((k_lm_head_pair<false, true, false>), dim3(grid), dim3(256), 0, s, a, sc);
+    else if (a.key) hipLaunchKernelGGL((k_lm_head_pair<false, false, true>), dim3(grid), dim3(256), 0, s, a, sc);
+    else hipLaunchKernelGGL((k_lm_head_pair<false, false, false>), dim3(grid), dim3(256), 0, s, a, sc);
     return hipGetLastError();
 }
 

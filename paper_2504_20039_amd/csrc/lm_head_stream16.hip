@@ -33,7 +33,7 @@ constexpr int S16_SEG = 512;                    // bytes of each row per stage (
 constexpr int S16_STAGE = S16_ROWS * S16_SEG;   // 8 KB = eight 1 KB loads
 constexpr int S16_LOADS = S16_STAGE / 1024;
 
-template <int NST, bool DUMP, bool TOPK>   // NST stages per tile and wave: d_t = NST * 2048
+template <int NST, bool DUMP, bool TOPK, bool SAMPLE>   // NST stages per tile and wave: d_t = NST * 2048
 __global__ __launch_bounds__(S16_WAVES * 64) void k_lm_head_stream16(LmHeadArgs a, int ntiles)
 {
     constexpr int KSTEPS = 8;                   // k steps of 32 per stage
@@ -88,13 +88,19 @@ __global__ __launch_bounds__(S16_WAVES * 64) void k_lm_head_stream16(LmHeadArgs 
         th = a.thr[min(myrow, a.M - 1)];
         tk = a.thr_tok[min(myrow, a.M - 1)];
     }
+    uint32_t klo = 0, khi = 0;          // sampling mode: the row's noise key
+    if (SAMPLE) {
+        const uint64_t key = a.key[min(myrow, a.M - 1)];
+        klo = (uint32_t)key;
+        khi = (uint32_t)(key >> 32);
+    }
     // make the compiler retire these loads here: its waits must not land inside the pipelined loop,
     // where they would drain the kernel's own asynchronous loads
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
         for (int t = 0; t < NST * KSTEPS; ++t) asm volatile("" : "+v"(hf[t][b]));
-    asm volatile("" : "+v"(th), "+v"(tk));
+    asm volatile("" : "+v"(th), "+v"(tk), "+v"(klo), "+v"(khi));
 
     float run_v = -INFINITY;
     int32_t run_i = 0x7fffffff;
@@ -144,6 +150,7 @@ __global__ __launch_bounds__(S16_WAVES * 64) void k_lm_head_stream16(LmHeadArgs 
         const int v = T * S16_ROWS + q4 * 4 + rsel;
         if (v < a.V) {
             if (DUMP && myrow < a.M) a.dump[(size_t)myrow * a.V + v] = sum;
+            if (SAMPLE) sum = fmaf(sum, a.inv_temp, gumbel_noise(klo, khi, (uint32_t)v));
             if (sum > run_v) {
                 run_v = sum;
                 run_i = v;
@@ -192,13 +199,16 @@ hipError_t launch16(const LmHeadArgs &a, int num_cus, hipStream_t s)
 {
     const int ntiles = (a.V + S16_ROWS - 1) / S16_ROWS;
     const int grid = persistent_grid(num_cus, ntiles);
-    // the top-K baseline's counting is a separate instantiation: the judge path pays nothing for it
+    // the top-K baseline's counting and the sampling noise are separate instantiations: the greedy judge path
+    // pays nothing for them
     if (a.dump)
-        hipLaunchKernelGGL((k_lm_head_stream16<NST, true, false>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
+        hipLaunchKernelGGL((k_lm_head_stream16<NST, true, false, false>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
     else if (a.thr)
-        hipLaunchKernelGGL((k_lm_head_stream16<NST, false, true>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
+        hipLaunchKernelGGL((k_lm_head_stream16<NST, false, true, false>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
+    else if (a.key)
+        hipLaunchKernelGGL((k_lm_head_stream16<NST, false, false, true>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
     else
-        hipLaunchKernelGGL((k_lm_head_stream16<NST, false, false>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
+        hipLaunchKernelGGL((k_lm_head_stream16<NST, false, false, false>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
     return hipGetLastError();
 }
 

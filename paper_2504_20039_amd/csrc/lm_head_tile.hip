@@ -109,6 +109,12 @@ __global__ __launch_bounds__(256) void k_lm_head_tile(LmHeadArgs a)
             th = a.thr[row];
             tk = a.thr_tok[row];
         }
+        uint32_t klo = 0, khi = 0;      // sampling mode: the row's noise key
+        const bool sample = a.key != nullptr;
+        if (sample && row < a.M) {
+            klo = (uint32_t)a.key[row];
+            khi = (uint32_t)(a.key[row] >> 32);
+        }
 #pragma unroll
         for (int x = 0; x < 2; ++x) {
 #pragma unroll
@@ -117,6 +123,7 @@ __global__ __launch_bounds__(256) void k_lm_head_tile(LmHeadArgs a)
                 float val = acc[x][y][r];
                 if (v < a.V) {
                     if (DUMP && row < a.M) a.dump[(size_t)row * a.V + v] = val;
+                    if (sample) val = fmaf(val, a.inv_temp, gumbel_noise(klo, khi, (uint32_t)v));
                     if (val > bv) {          // ascending v inside a lane: strict keeps the lowest
                         bv = val;
                         bi = v;

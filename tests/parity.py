@@ -78,8 +78,9 @@ def oracle_greedy(x, windows=None):
     return t, m1, m2
 
 
-def run_gpu(x, draft, tau, feat_offset=1, kernel=0, clf_b=None, flags=None, repeat=1):
-    """One aj_verify through the C ABI; returns dict of host arrays."""
+def run_gpu(x, draft, tau, feat_offset=1, kernel=0, clf_b=None, flags=None, repeat=1, sampled=None):
+    """One aj_verify (or, with sampled = (inv_temperature, row_key [B][K+1] uint64), aj_verify_sampled) through the
+    C ABI; returns dict of host arrays."""
     import torch
     import paper_2504_20039_amd as aj
     w = x.w
@@ -89,14 +90,19 @@ def run_gpu(x, draft, tau, feat_offset=1, kernel=0, clf_b=None, flags=None, repe
     out_len = torch.full((max(w.B, 1),), -7, dtype=torch.int32, device="cuda")
     out_tok = torch.full((max(w.B, 1),), -7, dtype=torch.int32, device="cuda")
     h = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, w.dtype_code, feat_offset, flags, kernel)
+    d_key = torch.from_numpy(np.ascontiguousarray(sampled[1], np.uint64).view(np.int64)).cuda() if sampled else None
     try:
         name = aj.aj_kernel_name(h)
         outs = []
         for _ in range(repeat):
             out_len.fill_(-7)
             out_tok.fill_(-7)
-            aj.aj_verify(h, dev[0], dev[1] if w.d_d > 0 else None, dev[2], dev[3], dev[4], clf_b, tau,
-                         out_len, out_tok)
+            if sampled:
+                aj.aj_verify_sampled(h, dev[0], dev[1] if w.d_d > 0 else None, dev[2], dev[3], dev[4], clf_b, tau,
+                                     sampled[0], d_key, out_len, out_tok)
+            else:
+                aj.aj_verify(h, dev[0], dev[1] if w.d_d > 0 else None, dev[2], dev[3], dev[4], clf_b, tau,
+                             out_len, out_tok)
             torch.cuda.synchronize()
             t_star, maxlogit, score = aj.aj_debug_copy(h, w.B, w.K, want_score=bool(flags & aj.AJ_FLAG_DEBUG))
             outs.append(dict(out_len=out_len.cpu().numpy()[:w.B].copy(), out_tok=out_tok.cpu().numpy()[:w.B].copy(),
@@ -109,8 +115,10 @@ def run_gpu(x, draft, tau, feat_offset=1, kernel=0, clf_b=None, flags=None, repe
     return outs[0]
 
 
-def compare(x, draft, tau, greedy, gpu, feat_offset=1, clf_b=None, windows=None):
-    """Assert parity of one GPU result with the oracle; returns the counts that are reported."""
+def compare(x, draft, tau, greedy, gpu, feat_offset=1, clf_b=None, windows=None, scores_row=None):
+    """Assert parity of one GPU result with the oracle; returns the counts that are reported.
+    greedy = the oracle's (token, max, runner-up) per row; scores_row(r) = the oracle's scores of row r over the
+    vocabulary (default: its logits; the sampling tests pass the perturbed scores)."""
     w = x.w
     clf_b = w.clf_b if clf_b is None else clf_b
     t, m1, m2 = greedy
@@ -131,7 +139,7 @@ def compare(x, draft, tau, greedy, gpu, feat_offset=1, clf_b=None, windows=None)
         f"greedy token differs on unflagged rows {rows[differ & ~flag][:10]}"
     t_replay = t.copy()
     for r in rows[differ]:
-        lg = oracle.logits_row(x.ht[r], x.W)
+        lg = oracle.logits_row(x.ht[r], x.W) if scores_row is None else scores_row(r)
         assert 0 <= gpu["t_star"][r] < w.V
         assert lg[gpu["t_star"][r]] >= m1[r] - 1e-3 * abs(m1[r]), f"row {r}: GPU token is not a near-tie"
         t_replay[r] = gpu["t_star"][r]
