@@ -307,6 +307,7 @@ hipError_t lm_head_pair_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s)
     const int grid = persistent_grid(num_cus, sc.total);
     // the top-K baseline's counting and the sampling noise are separate instantiations: the greedy judge path
     // pays nothing for them
+    // (non-temporal W_lm loads for a single row tile were tried here as in the streaming kernel: no measurable change)
     if (a.dump) hipLaunchKernelGGL((k_lm_head_pair<true, false, false>), dim3(grid), dim3(256), 0, s, a, sc);
     else if (a.thr) hipLaunchKernelGGL((k_lm_head_pair<false, true, false>), dim3(grid), dim3(256), 0, s, a, sc);
     else if (a.key) hipLaunchKernelGGL((k_lm_head_pair<false, false, true>), dim3(grid), dim3(256), 0, s, a, sc);
