@@ -80,7 +80,7 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
     if (c.B < 0 || c.K < 1 || c.K > 1023 || c.V < 1 || c.d_t < mult || c.d_d < 0) return AJ_EINVAL;
     if (c.d_t % mult || c.d_d % mult) return AJ_EINVAL;
     if (c.feat_offset != 0 && c.feat_offset != 1) return AJ_EINVAL;
-    if (c.kernel < AJ_KERNEL_AUTO || c.kernel > AJ_KERNEL_PAIR) return AJ_EINVAL;
+    if (c.kernel < AJ_KERNEL_AUTO || c.kernel > AJ_KERNEL_PAIR9) return AJ_EINVAL;
     if ((int64_t)c.B * (c.K + 1) > (int64_t)1 << 24) return AJ_EINVAL;
 
     aj_handle *h = new (std::nothrow) aj_handle();
@@ -127,7 +127,7 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
             else if (pair) v = AJ_KERNEL_PAIR;
             else if (big) v = AJ_KERNEL_BIG;
             else v = AJ_KERNEL_TILE;
-        } else if (v == AJ_KERNEL_PAIR ? (h->M > 0 && !lm_head_pair_supports(h->M, c.V, c.d_t))
+        } else if (v == AJ_KERNEL_PAIR || v == AJ_KERNEL_PAIR9 ? (h->M > 0 && !lm_head_pair_supports(h->M, c.V, c.d_t))
                    : v != AJ_KERNEL_TILE && h->M > 0 && !lm_head_mfma_supports(v, h->M, c.V, c.d_t) &&
                          !(v == AJ_KERNEL_STREAM && lm_head_stream16_supports(h->M, c.V, c.d_t))) {
             delete h;
@@ -137,6 +137,7 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
         h->stream16 = v == AJ_KERNEL_STREAM && lm_head_stream16_supports(h->M, c.V, c.d_t);
         h->nblocks = v == AJ_KERNEL_TILE ? lm_head_tile_blocks(c.V)
                      : v == AJ_KERNEL_PAIR ? lm_head_pair_blocks(c.V)
+                     : v == AJ_KERNEL_PAIR9 ? lm_head_pair9_blocks(c.V)
                      : h->stream16     ? lm_head_stream16_blocks(c.V, h->num_cus)
                                        : lm_head_mfma_blocks(v, c.V, c.d_t, h->num_cus);
     }
@@ -207,6 +208,7 @@ static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void 
     if (h->variant == AJ_KERNEL_TILE) return lm_head_tile_bf16(a, s);
     if (h->stream16) return lm_head_stream16_bf16(a, h->num_cus, s);
     if (h->variant == AJ_KERNEL_PAIR) return lm_head_pair_bf16(a, h->num_cus, s);
+    if (h->variant == AJ_KERNEL_PAIR9) return lm_head_pair9_bf16(a, h->num_cus, s);
     return lm_head_mfma_bf16(h->variant, a, h->num_cus, s);
 }
 
@@ -396,6 +398,7 @@ extern "C" const char *aj_kernel_name(const aj_handle *h)
         case AJ_KERNEL_BIG: return "lm_head_big_bf16";
         case AJ_KERNEL_TALL: return "lm_head_tall_bf16";
         case AJ_KERNEL_PAIR: return "lm_head_pair_bf16";
+        case AJ_KERNEL_PAIR9: return "lm_head_pair9_bf16";
         default: return "unknown";
     }
 }

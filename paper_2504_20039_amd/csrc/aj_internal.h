@@ -91,6 +91,12 @@ int lm_head_pair_blocks(int V);
 int lm_head_pair_padded_rows(int M);
 hipError_t lm_head_pair_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s);
 
+// 256 x 288 tiles, same operand pipeline, 4 waves of 64 x 288 (257..288 verify rows in one row tile)
+bool lm_head_pair9_supports(int M, int V, int d);
+int lm_head_pair9_blocks(int V);
+int lm_head_pair9_padded_rows(int M);
+hipError_t lm_head_pair9_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s);
+
 struct TailArgs {
     const void *hidden_t, *hidden_d, *clf_w;
     const int32_t *draft_tok;

@@ -9,7 +9,7 @@ from parity import compare, make_inputs, oracle_greedy, parity_case, run_gpu
 pytestmark = pytest.mark.gpu
 
 TINY = wl.WORKLOADS["tiny_f32"]
-KERNELS_BF16 = [1, 2, 3, 4, 5]    # AJ_KERNEL_TILE, _STREAM, _BIG, _TALL, _PAIR (forced); 0 = AUTO is covered too
+KERNELS_BF16 = [1, 2, 3, 4, 5, 6] # AJ_KERNEL_TILE, _STREAM, _BIG, _TALL, _PAIR, _PAIR9 (forced); 0 = AUTO is covered too
 
 
 def _skip_unless_supported(w, kernel):
@@ -282,6 +282,7 @@ def test_profile_events_and_kernel_names():
     (3, dict(B=8, K=31, d_t=512, d_d=64, V=5000)),
     (4, dict(B=9, K=31, d_t=512, d_d=64, V=5000)),
     (5, dict(B=9, K=31, d_t=768, d_d=64, V=5000)),
+    (6, dict(B=9, K=31, d_t=768, d_d=64, V=5000)),
 ])
 def test_run_to_run_bit_identical(kernel, shape):
     w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="det", p_match=0.5, **shape)

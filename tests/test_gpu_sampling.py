@@ -51,7 +51,7 @@ def test_tiny_f32_and_the_noise_matters():
     assert np.array_equal(cold["t_star"], oracle.sampled_rows(x.ht, x.W, 0.0, keys.reshape(-1))[0])
 
 
-@pytest.mark.parametrize("kernel", [0, 1, 2, 3, 4, 5])
+@pytest.mark.parametrize("kernel", [0, 1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("shape", [
     dict(B=1, K=16, d_t=4096, d_d=64, V=5003),         # 16-row streaming kernel, ragged vocabulary
     dict(B=2, K=15, d_t=384, d_d=64, V=20000),         # streaming regime at another hidden size

@@ -97,7 +97,7 @@ def test_tiny_f32():
     assert (gpu[w.V]["out_len"] == w.K).all()
 
 
-@pytest.mark.parametrize("kernel", [0, 1, 2, 3, 4, 5])
+@pytest.mark.parametrize("kernel", [0, 1, 2, 3, 4, 5, 6])
 @pytest.mark.parametrize("shape", [
     dict(B=1, K=16, d_t=4096, d_d=64, V=5003),         # 16-row streaming kernel, ragged vocabulary
     dict(B=2, K=15, d_t=384, d_d=64, V=20000),         # streaming regime at another hidden size
