@@ -107,26 +107,35 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
     } else {
         int v = c.kernel;
         if (v == AJ_KERNEL_AUTO) {
-            // W_lm-streaming regime while one 32-row block holds every verify row.  Above that, one of the
-            // large-tile kernels: 256-row tiles (4 waves, hand-scheduled) or, beyond 256 rows, 288/320-row
-            // tiles (8 waves) when they cost less - padded rows are wasted MFMA work, and a batch of 257..320
-            // rows in ONE row tile reads W_lm from HBM only once.  Per padded row the 256-row kernel that
-            // loads whole 128-byte lines (d_t a multiple of 256) is about 15 % faster than the 8-wave kernel
-            // and the other 256-row kernel about 4 % (measured on the same device), so the taller tiles must
-            // save more rows than that.  Below 256 rows a single padded 256-row tile still wins: the step is
-            // bound by streaming W_lm, which these pipelines do at 4.2-4.9 TB/s against 2.2-3.8 TB/s of the
-            // general 128 x 128 kernel (34..255 rows, same device).  The general kernel serves what is left:
-            // hidden sizes that are not a multiple of 32.
-            const bool big = lm_head_mfma_supports(AJ_KERNEL_BIG, h->M, c.V, c.d_t);
-            const bool pair = lm_head_pair_supports(h->M, c.V, c.d_t);
-            const bool tall = h->M > 256 && lm_head_mfma_supports(AJ_KERNEL_TALL, h->M, c.V, c.d_t);
-            const double tall_cost = (pair ? 1.15 : 1.04) * lm_head_mfma_padded_rows(AJ_KERNEL_TALL, h->M);
+            // W_lm-streaming regime while one 32-row block holds every verify row.  Above that, the large-tile
+            // kernel with the lowest cost = padded row count x a per-row factor measured on one device against
+            // the 256-row whole-line kernel (PAIR = 1): its 288-row variant 1.06, the 256-row kernel with
+            // 64-byte pieces 1.10, the 8-wave 288/320-row kernel 1.15.  Padded rows are wasted MFMA work, and a
+            // batch of 257..320 rows in ONE row tile reads W_lm from HBM only once.  Below 256 rows a single
+            // padded tile still wins over the general 128 x 128 kernel: the step is bound by streaming W_lm,
+            // which these pipelines do at 4.2-4.9 TB/s against 2.2-3.8 (34..255 rows, same device).  The general
+            // kernel serves what is left: hidden sizes that are not a multiple of 32.
             if (lm_head_stream16_supports(h->M, c.V, c.d_t) ||
-                lm_head_mfma_supports(AJ_KERNEL_STREAM, h->M, c.V, c.d_t)) v = AJ_KERNEL_STREAM;
-            else if (tall && (!(big || pair) || tall_cost < lm_head_pair_padded_rows(h->M))) v = AJ_KERNEL_TALL;
-            else if (pair) v = AJ_KERNEL_PAIR;
-            else if (big) v = AJ_KERNEL_BIG;
-            else v = AJ_KERNEL_TILE;
+                lm_head_mfma_supports(AJ_KERNEL_STREAM, h->M, c.V, c.d_t)) {
+                v = AJ_KERNEL_STREAM;
+            } else {
+                const bool pair = lm_head_pair_supports(h->M, c.V, c.d_t);
+                struct { int kernel; bool ok; double cost; } cand[4] = {
+                    {AJ_KERNEL_PAIR, pair, 1.00 * lm_head_pair_padded_rows(h->M)},
+                    {AJ_KERNEL_PAIR9, pair, 1.06 * lm_head_pair9_padded_rows(h->M)},
+                    {AJ_KERNEL_BIG, lm_head_mfma_supports(AJ_KERNEL_BIG, h->M, c.V, c.d_t),
+                     1.10 * lm_head_mfma_padded_rows(AJ_KERNEL_BIG, h->M)},
+                    {AJ_KERNEL_TALL, lm_head_mfma_supports(AJ_KERNEL_TALL, h->M, c.V, c.d_t),
+                     1.15 * lm_head_mfma_padded_rows(AJ_KERNEL_TALL, h->M)},
+                };
+                v = AJ_KERNEL_TILE;
+                double best = 0.0;
+                for (const auto &k : cand)
+                    if (k.ok && (v == AJ_KERNEL_TILE || k.cost < best)) {
+                        v = k.kernel;
+                        best = k.cost;
+                    }
+            }
         } else if (v == AJ_KERNEL_PAIR || v == AJ_KERNEL_PAIR9 ? (h->M > 0 && !lm_head_pair_supports(h->M, c.V, c.d_t))
                    : v != AJ_KERNEL_TILE && h->M > 0 && !lm_head_mfma_supports(v, h->M, c.V, c.d_t) &&
                          !(v == AJ_KERNEL_STREAM && lm_head_stream16_supports(h->M, c.V, c.d_t))) {

@@ -270,9 +270,11 @@ def test_profile_events_and_kernel_names():
     with pytest.raises(aj.AjError):
         aj.aj_profile_read(plain)
     aj.aj_destroy(plain)
-    for M_B, d_t, name in ((8, 4096, "lm_head_pair_bf16"), (8, 4096 + 64, "lm_head_big_bf16"), (4, 4096, "lm_head_pair_bf16"), (4, 4096 + 8, "lm_head_tile_bf16"),
-                           (9, 4096, "lm_head_tall_bf16"), (33, 4096, "lm_head_pair_bf16"), (33, 4096 + 64, "lm_head_tall_bf16")):
-        hh = aj.aj_create(M_B, 31, d_t, 64, 4096, aj.AJ_BF16)     # 256, 256, 128, 128, 288, 1056, 1056 verify rows
+    for M_B, d_t, name in ((8, 4096, "lm_head_pair_bf16"), (8, 4096 + 64, "lm_head_big_bf16"), (4, 4096, "lm_head_pair_bf16"),
+                           (4, 4096 + 8, "lm_head_tile_bf16"), (9, 4096, "lm_head_pair9_bf16"), (10, 4096, "lm_head_tall_bf16"),
+                           (33, 4096, "lm_head_pair9_bf16"), (33, 4096 + 64, "lm_head_tall_bf16"),
+                           (260, 4096, "lm_head_pair_bf16")):
+        hh = aj.aj_create(M_B, 31, d_t, 64, 4096, aj.AJ_BF16)     # 256, 256, 128, 128, 288, 320, 1056, 1056, 8320 verify rows
         assert aj.aj_kernel_name(hh) == name, (M_B, aj.aj_kernel_name(hh))
         aj.aj_destroy(hh)
 
