@@ -59,6 +59,10 @@ def _load():
         lib.ajo_walk_topk.restype = i32
         lib.ajo_verify_topk.argtypes = [i32] * 6 + [vp] * 10
         lib.ajo_verify_topk.restype = i32
+        lib.ajo_walk_tree.argtypes = [i32] * 6 + [vp] * 6 + [flt, flt] + [vp] * 7
+        lib.ajo_walk_tree.restype = i32
+        lib.ajo_verify_tree.argtypes = [i32] * 7 + [vp] * 6 + [flt, flt] + [vp] * 10
+        lib.ajo_verify_tree.restype = i32
         lib.ajo_gumbel.argtypes = [ctypes.c_uint64, i32]
         lib.ajo_gumbel.restype = dbl
         lib.ajo_sampled_rows.argtypes = [i32, vp, i32, vp, i32, i32, dbl, vp, vp, vp, vp]
@@ -318,4 +322,59 @@ def verify_sampled(hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, inv_t
                                     _ptr(r.near_tie), _ptr(r.mismatch), _ptr(r.z), _ptr(r.p), _ptr(r.near_thr))
     if rc:
         raise ValueError(f"ajo_verify_sampled rc={rc}")
+    return r
+
+
+# ---- draft trees (Section 3.3 "Generality": the judge on a tree-based verification stage)
+
+class TreeResult:
+    __slots__ = ("out_len", "out_tok", "out_node", "t_star", "max1", "max2", "mismatch", "z", "p", "near_thr")
+
+
+def walk_tree(hidden_t, hidden_d, t_star, draft_tok, parent, clf_w, clf_b, tau, feat_offset=1) -> TreeResult:
+    """Longest accepted root-to-node path per window, given the greedy tokens t_star [B][K+1]."""
+    draft_tok, parent = _c(draft_tok, np.int32), _c(parent, np.int32)
+    B, K = draft_tok.shape
+    assert parent.shape == (B, K)
+    clf_w = _c(clf_w)
+    t_star = _c(t_star, np.int32).reshape(B, K + 1)
+    hidden_t = _c(hidden_t).reshape(B, K + 1, -1)
+    d_t = hidden_t.shape[2]
+    d_d = clf_w.shape[0] - d_t
+    hidden_d = _c(hidden_d).reshape(B, K + 1, d_d) if d_d > 0 else None
+    r = TreeResult()
+    r.out_len, r.out_tok, r.out_node = np.empty(B, np.int32), np.empty(B, np.int32), np.empty(B, np.int32)
+    r.mismatch, r.near_thr = np.empty((B, K), np.uint8), np.empty((B, K), np.uint8)
+    r.z, r.p = np.empty((B, K), np.float64), np.empty((B, K), np.float64)
+    rc = _load().ajo_walk_tree(B, K, d_t, d_d, _code(hidden_t), feat_offset, _ptr(hidden_t), _ptr(hidden_d),
+                               _ptr(t_star), _ptr(draft_tok), _ptr(parent), _ptr(clf_w), float(clf_b), float(tau),
+                               _ptr(r.out_len), _ptr(r.out_tok), _ptr(r.out_node),
+                               _ptr(r.mismatch), _ptr(r.z), _ptr(r.p), _ptr(r.near_thr))
+    if rc:
+        raise ValueError(f"ajo_walk_tree rc={rc}")
+    return r
+
+
+def verify_tree(hidden_t, hidden_d, W_lm, draft_tok, parent, clf_w, clf_b, tau, feat_offset=1) -> TreeResult:
+    """The whole step on draft trees, with diagnostics."""
+    draft_tok, parent = _c(draft_tok, np.int32), _c(parent, np.int32)
+    B, K = draft_tok.shape
+    W_lm, clf_w = _c(W_lm), _c(clf_w)
+    V, d_t = W_lm.shape
+    d_d = clf_w.shape[0] - d_t
+    hidden_t = _c(hidden_t).reshape(B, K + 1, d_t)
+    hidden_d = _c(hidden_d).reshape(B, K + 1, d_d) if d_d > 0 else None
+    M = B * (K + 1)
+    r = TreeResult()
+    r.out_len, r.out_tok, r.out_node = np.empty(B, np.int32), np.empty(B, np.int32), np.empty(B, np.int32)
+    r.t_star, r.max1, r.max2 = np.empty(M, np.int32), np.empty(M, np.float64), np.empty(M, np.float64)
+    r.mismatch, r.near_thr = np.empty((B, K), np.uint8), np.empty((B, K), np.uint8)
+    r.z, r.p = np.empty((B, K), np.float64), np.empty((B, K), np.float64)
+    rc = _load().ajo_verify_tree(B, K, d_t, d_d, V, _code(W_lm), feat_offset, _ptr(hidden_t), _ptr(hidden_d),
+                                 _ptr(W_lm), _ptr(draft_tok), _ptr(parent), _ptr(clf_w), float(clf_b), float(tau),
+                                 _ptr(r.out_len), _ptr(r.out_tok), _ptr(r.out_node),
+                                 _ptr(r.t_star), _ptr(r.max1), _ptr(r.max2),
+                                 _ptr(r.mismatch), _ptr(r.z), _ptr(r.p), _ptr(r.near_thr))
+    if rc:
+        raise ValueError(f"ajo_verify_tree rc={rc}")
     return r

@@ -43,7 +43,8 @@
  * that file for the list.  The top-K baseline of Section 4 (ajo_rank_rows,
  * ajo_walk_topk, ajo_verify_topk, at the end of this file) is pinned in
  * tests/test_oracle_topk_pins.py, the sampling mode of Appendix A (ajo_gumbel,
- * ajo_sampled_rows, ajo_verify_sampled) in tests/test_oracle_sampling_pins.py.
+ * ajo_sampled_rows, ajo_verify_sampled) in tests/test_oracle_sampling_pins.py, draft trees
+ * (ajo_walk_tree, ajo_verify_tree) in tests/test_oracle_tree_pins.py.
  */
 #include <math.h>
 #include <stdint.h>
@@ -566,6 +567,125 @@ int ajo_verify_sampled(int B, int K, int d_t, int d_d, int V, int dtype, int fea
                 if (near_tie) near_tie[r] = (uint8_t)((m1[r] - m2[r]) < AJO_NEAR_TIE_REL * fabs(m1[r]));
             }
         }
+    }
+    free(t);
+    free(m1);
+    free(m2);
+    return rc;
+}
+
+/* ------------------------------------------------------------------ tree drafts (Section 3.3, "Generality") */
+
+/*
+ * Section 3.3 ("Generality") states that the judge applies to any speculative decoding
+ * algorithm with a verification stage, tree-based ones included, and gives no further detail;
+ * the rule below is that section's rule (call the classifier where the base algorithm would
+ * reject, accept if unimportant, keep verifying) applied edge by edge to a draft tree.
+ *
+ * A window is a tree of K draft nodes.  parent[j] in [-1, j) is node j's parent (-1 = the root,
+ * i.e. the context; parents come before children).  Verify row 0 is the root's state and row
+ * j+1 the state that has consumed node j's token, so the target's prediction that node j is
+ * checked against is t_star[row(parent[j])] with row(-1) = 0, row(p) = p + 1, and the state
+ * that ENCODES node j's token (the judge's features, feat_offset = 1) is row j + 1; with
+ * feat_offset = 0 the features are the state that predicted the token, row(parent[j]).
+ *
+ *   edge_ok[j]  = (draft_tok[j] == t_star[row(parent[j])])  or  judge logit z_j < logit(tau)
+ *   accepted[j] = edge_ok[j] and (parent[j] == -1 or accepted[parent[j]])
+ *   out_node    = the accepted node of greatest depth, lowest index among equals (-1: none)
+ *   out_len     = its depth (number of tokens on the accepted path), out_tok = t_star[row(out_node)]
+ *
+ * With parent[j] = j - 1 (a chain) this is ajo_walk; with tau = 0 it is plain greedy tree
+ * verification.  Diagnostics as in ajo_walk, per node.  Returns -1 for a parent outside [-1, j).
+ */
+int ajo_walk_tree(int B, int K, int d_t, int d_d, int dtype, int feat_offset,
+                  const void *hidden_t, const void *hidden_d, const int32_t *t_star,
+                  const int32_t *draft_tok, const int32_t *parent, const void *clf_w, float clf_b, float tau,
+                  int32_t *out_len, int32_t *out_tok, int32_t *out_node,
+                  uint8_t *mismatch, double *z_out, double *p_out, uint8_t *near_thr)
+{
+    if (B < 0 || K < 1 || d_t <= 0 || d_d < 0 || (feat_offset != 0 && feat_offset != 1))
+        return -1;
+    if (!hidden_t || (d_d > 0 && !hidden_d) || !t_star || !draft_tok || !parent || !clf_w || !out_len ||
+        !out_tok || !out_node)
+        return -1;
+    if (!(tau >= 0.0f && tau <= 1.0f))
+        return -1;
+    for (int b = 0; b < B; ++b)
+        for (int j = 0; j < K; ++j) {
+            int32_t p = parent[(size_t)b * (size_t)K + (size_t)j];
+            if (p < -1 || p >= j)
+                return -1;
+        }
+    const double zthr = ajo_threshold_logit((double)tau);
+    const size_t es = elem_size(dtype);
+    int32_t *depth = (int32_t *)malloc(sizeof(int32_t) * (size_t)K);   /* 0 = not accepted */
+    if (!depth)
+        return -2;
+    for (int b = 0; b < B; ++b) {
+        const int32_t *t = t_star + (size_t)b * (size_t)(K + 1);
+        int best = -1, best_depth = 0;
+        for (int j = 0; j < K; ++j) {
+            size_t s = (size_t)b * (size_t)K + (size_t)j;
+            int p = parent[s];
+            int prow = p + 1;                                      /* row(-1) = 0, row(p) = p + 1 */
+            int mis = (t[prow] != draft_tok[s]);
+            double z = NAN, pr = NAN;
+            int ok = 1, nthr = 0;
+            if (mis) {
+                size_t row = (size_t)b * (size_t)(K + 1) + (size_t)(feat_offset ? j + 1 : prow);
+                const char *ht = (const char *)hidden_t + row * (size_t)d_t * es;
+                const char *hd = d_d > 0 ? (const char *)hidden_d + row * (size_t)d_d * es : NULL;
+                z = ajo_judge_logit(dtype, ht, hd, clf_w, d_t, d_d, (double)clf_b);
+                pr = 1.0 / (1.0 + exp(-z));
+                ok = (z < zthr);
+                if (isfinite(zthr))
+                    nthr = fabs(z - zthr) < AJO_NEAR_THR_REL * fmax(1.0, fabs(z));
+            }
+            int pd = p < 0 ? 0 : depth[p];                         /* depth of the parent, 0 if not accepted */
+            depth[j] = (ok && (p < 0 || pd > 0)) ? pd + 1 : 0;
+            if (depth[j] > best_depth) {                           /* strict: lowest index among equal depths */
+                best_depth = depth[j];
+                best = j;
+            }
+            if (mismatch) mismatch[s] = (uint8_t)mis;
+            if (z_out) z_out[s] = z;
+            if (p_out) p_out[s] = pr;
+            if (near_thr) near_thr[s] = (uint8_t)nthr;
+        }
+        out_node[b] = best;
+        out_len[b] = best_depth;
+        out_tok[b] = t[best + 1];
+    }
+    free(depth);
+    return 0;
+}
+
+/* The whole step on draft trees: LM head and greedy tokens of all B*(K+1) rows, then ajo_walk_tree. */
+int ajo_verify_tree(int B, int K, int d_t, int d_d, int V, int dtype, int feat_offset,
+                    const void *hidden_t, const void *hidden_d, const void *W_lm,
+                    const int32_t *draft_tok, const int32_t *parent, const void *clf_w, float clf_b, float tau,
+                    int32_t *out_len, int32_t *out_tok, int32_t *out_node,
+                    int32_t *t_star_out, double *max1_out, double *max2_out,
+                    uint8_t *mismatch, double *z_out, double *p_out, uint8_t *near_thr)
+{
+    if (B < 0 || K < 1 || V <= 0)
+        return -1;
+    int M = B * (K + 1);
+    int32_t *t = (int32_t *)calloc((size_t)(M > 0 ? M : 1), sizeof(int32_t));
+    double *m1 = (double *)calloc((size_t)(M > 0 ? M : 1), sizeof(double));
+    double *m2 = (double *)calloc((size_t)(M > 0 ? M : 1), sizeof(double));
+    int rc = -2;
+    if (t && m1 && m2) {
+        rc = M > 0 ? ajo_greedy_rows(dtype, hidden_t, M, W_lm, V, d_t, t, m1, m2) : 0;
+        if (rc == 0)
+            rc = ajo_walk_tree(B, K, d_t, d_d, dtype, feat_offset, hidden_t, hidden_d, t, draft_tok, parent,
+                               clf_w, clf_b, tau, out_len, out_tok, out_node, mismatch, z_out, p_out, near_thr);
+        if (rc == 0)
+            for (int r = 0; r < M; ++r) {
+                if (t_star_out) t_star_out[r] = t[r];
+                if (max1_out) max1_out[r] = m1[r];
+                if (max2_out) max2_out[r] = m2[r];
+            }
     }
     free(t);
     free(m1);
