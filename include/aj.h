@@ -100,6 +100,27 @@ int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_d, const vo
               int32_t *out_len, int32_t *out_tok, void *stream);
 
 /*
+ * The same steps on draft TREES (Section 3.3, "Generality": the judge applies to tree-based verification
+ * stages as well; the rule of aj_verify is applied edge by edge).  The K slots of a window are tree nodes:
+ *   parent    [B][K] int32   device; parent[b][j] in [-1, j) is node j's parent (-1 = the root, i.e. the
+ *                            context); parents come before their children.  Values outside that range are
+ *                            clamped into it.
+ *   hidden_t / hidden_d      row 0 of a window = the root's state, row j+1 = the state that has consumed node
+ *                            j's token
+ * Node j is checked against the greedy token of its parent's row; at a mismatch the judge reads row j+1
+ * (feat_offset = 1; the parent's row with feat_offset = 0).  A node is accepted when its edge matches or is
+ * judged unimportant AND its parent is accepted.  Outputs per window:
+ *   out_node [B] int32       the accepted node of greatest depth, lowest index among equals; -1 if none
+ *   out_len  [B] int32       its depth (tokens on the accepted path, which parent[] spells out)
+ *   out_tok  [B] int32       greedy token of that node's row (of row 0 when out_node = -1)
+ * With parent[b][j] = j - 1 this is aj_verify; with tau = 0 it is greedy tree verification.
+ * Errors as aj_verify, plus AJ_EINVAL for a null parent or out_node.
+ */
+int aj_verify_tree(aj_handle *h, const void *hidden_t, const void *hidden_d, const void *W_lm,
+                   const int32_t *draft_tok, const int32_t *parent, const void *clf_w, float clf_b, float tau,
+                   int32_t *out_len, int32_t *out_tok, int32_t *out_node, void *stream);
+
+/*
  * The same steps for stochastic decoding, made a deterministic function of a random state with the
  * Gumbel-max trick (Appendix A, "Generalization to sampling"): the target's token of a verify row is
  *     y[r] = lowest v attaining max_v ( logit[r][v] * inv_temperature + G(row_key[r], v) )

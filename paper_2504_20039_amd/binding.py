@@ -18,7 +18,7 @@ AJ_F32, AJ_BF16 = 0, 1
 AJ_FLAG_DEBUG, AJ_FLAG_PROFILE, AJ_FLAG_TOPK = 1, 2, 4
 AJ_KERNEL_AUTO, AJ_KERNEL_TILE, AJ_KERNEL_STREAM, AJ_KERNEL_BIG, AJ_KERNEL_TALL, AJ_KERNEL_PAIR, AJ_KERNEL_PAIR9 = 0, 1, 2, 3, 4, 5, 6
 
-SYMBOLS = ["aj_create", "aj_verify", "aj_verify_sampled", "aj_verify_topk", "aj_debug_copy_rank", "aj_destroy", "aj_debug_ptrs", "aj_debug_copy", "aj_debug_logits",
+SYMBOLS = ["aj_create", "aj_verify", "aj_verify_sampled", "aj_verify_tree", "aj_verify_topk", "aj_debug_copy_rank", "aj_destroy", "aj_debug_ptrs", "aj_debug_copy", "aj_debug_logits",
            "aj_profile_read", "aj_kernel_name", "aj_strerror", "aj_last_hip_error"]
 
 
@@ -59,6 +59,8 @@ def load_library():
     lib.aj_verify.restype = ctypes.c_int
     lib.aj_verify_sampled.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, f32, vp, vp, vp, vp]
     lib.aj_verify_sampled.restype = ctypes.c_int
+    lib.aj_verify_tree.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp]
+    lib.aj_verify_tree.restype = ctypes.c_int
     lib.aj_verify_topk.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
     lib.aj_verify_topk.restype = ctypes.c_int
     lib.aj_debug_copy_rank.argtypes = [vp, vp, vp]
@@ -139,6 +141,15 @@ def aj_verify_sampled(h, hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau,
                                           _ptr(row_key), _ptr(out_len), _ptr(out_tok), _stream(stream))
     if rc != 0:
         raise AjError(rc, "aj_verify_sampled")
+
+
+def aj_verify_tree(h, hidden_t, hidden_d, W_lm, draft_tok, parent, clf_w, clf_b, tau, out_len, out_tok, out_node,
+                   stream=None):
+    rc = load_library().aj_verify_tree(h, _ptr(hidden_t), _ptr(hidden_d), _ptr(W_lm), _ptr(draft_tok), _ptr(parent),
+                                       _ptr(clf_w), float(clf_b), float(tau), _ptr(out_len), _ptr(out_tok),
+                                       _ptr(out_node), _stream(stream))
+    if rc != 0:
+        raise AjError(rc, "aj_verify_tree")
 
 
 def aj_verify_topk(h, hidden_t, W_lm, draft_tok, top_k, out_len, out_tok, stream=None):

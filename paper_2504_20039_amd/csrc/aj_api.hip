@@ -221,10 +221,12 @@ static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void 
     return lm_head_mfma_bf16(h->variant, a, h->num_cus, s);
 }
 
-// aj_verify and aj_verify_sampled: the same steps; key == nullptr selects the greedy token
+// aj_verify, aj_verify_sampled and aj_verify_tree: the same steps; key == nullptr selects the greedy token,
+// parent == nullptr a chain of draft tokens
 static int verify_common(aj_handle *h, const void *hidden_t, const void *hidden_d, const void *W_lm,
                          const int32_t *draft_tok, const void *clf_w, float clf_b, float tau,
-                         const uint64_t *key, float inv_temp, int32_t *out_len, int32_t *out_tok, void *stream)
+                         const uint64_t *key, float inv_temp, const int32_t *parent, int32_t *out_node,
+                         int32_t *out_len, int32_t *out_tok, void *stream)
 {
     if (!h) return AJ_EINVAL;
     if (!(tau >= 0.f && tau <= 1.f)) return AJ_EINVAL;   // also refuses NaN
@@ -267,6 +269,8 @@ static int verify_common(aj_handle *h, const void *hidden_t, const void *hidden_
     t.score = h->score;
     t.out_len = out_len;
     t.out_tok = out_tok;
+    t.parent = parent;
+    t.out_node = out_node;
     if ((e = verify_tail(t, s)) != hipSuccess) return hip_fail(e);
     return AJ_OK;
 }
@@ -275,8 +279,18 @@ extern "C" int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_
                          const int32_t *draft_tok, const void *clf_w, float clf_b, float tau,
                          int32_t *out_len, int32_t *out_tok, void *stream)
 {
-    return verify_common(h, hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, nullptr, 1.f, out_len, out_tok,
-                         stream);
+    return verify_common(h, hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, nullptr, 1.f, nullptr, nullptr,
+                         out_len, out_tok, stream);
+}
+
+extern "C" int aj_verify_tree(aj_handle *h, const void *hidden_t, const void *hidden_d, const void *W_lm,
+                              const int32_t *draft_tok, const int32_t *parent, const void *clf_w, float clf_b,
+                              float tau, int32_t *out_len, int32_t *out_tok, int32_t *out_node, void *stream)
+{
+    if (!h) return AJ_EINVAL;
+    if (h->M > 0 && (!parent || !out_node)) return AJ_EINVAL;
+    return verify_common(h, hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, nullptr, 1.f, parent, out_node,
+                         out_len, out_tok, stream);
 }
 
 extern "C" int aj_verify_sampled(aj_handle *h, const void *hidden_t, const void *hidden_d, const void *W_lm,
@@ -287,8 +301,8 @@ extern "C" int aj_verify_sampled(aj_handle *h, const void *hidden_t, const void 
     if (!h) return AJ_EINVAL;
     if (!(inv_temperature >= 0.f) || !isfinite(inv_temperature)) return AJ_EINVAL;
     if (h->M > 0 && (!row_key || (((uintptr_t)row_key) & 7u))) return AJ_EINVAL;
-    return verify_common(h, hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, row_key, inv_temperature, out_len,
-                         out_tok, stream);
+    return verify_common(h, hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, row_key, inv_temperature, nullptr,
+                         nullptr, out_len, out_tok, stream);
 }
 
 extern "C" int aj_verify_topk(aj_handle *h, const void *hidden_t, const void *W_lm, const int32_t *draft_tok,

@@ -108,6 +108,9 @@ struct TailArgs {
     float *maxlogit;        // [M] out
     float *score;           // [B][K] out or nullptr
     int32_t *out_len, *out_tok;
+    // draft trees (nullptr for chains): parent[B][K] in [-1, j), and the accepted node per window
+    const int32_t *parent;
+    int32_t *out_node;
 };
 hipError_t verify_tail(const TailArgs &a, hipStream_t s);     // partials -> t_star; steps 3-4
 

@@ -52,7 +52,9 @@ __device__ __forceinline__ float dot_part(const void *x, const void *w, int n, i
 // Phase 2: a wave per slot; at a mismatching slot (wave-uniform) its lanes share the judge dot
 //          product and reduce it with cross-lane shuffles.
 // Phase 3: wave 0 finds the first rejected slot with ballots and emits.
-template <bool BF16>
+// TREE: the K slots are nodes of a draft tree (a.parent[b][j] in [-1, j)): node j is checked against the
+//          greedy token of its parent's row, phase 3 finds the accepted node of greatest depth.
+template <bool BF16, bool TREE>
 __global__ __launch_bounds__(TAIL_WAVES * 64) void k_verify_tail(TailArgs a)
 {
     __shared__ int32_t s_t[MAXK + 1];
@@ -98,11 +100,14 @@ __global__ __launch_bounds__(TAIL_WAVES * 64) void k_verify_tail(TailArgs a)
     __syncthreads();
 
     for (int j = wave; j < K; j += TAIL_WAVES) {
-        const bool mis = s_t[j] != a.draft_tok[(size_t)b * K + j];
+        // row whose prediction slot j is checked against: j in a chain, the parent's row in a tree
+        // (a parent outside [-1, j) is clamped into it: malformed input stays inside the window's rows)
+        const int prow = TREE ? min(max(a.parent[(size_t)b * K + j], -1), j - 1) + 1 : j;
+        const bool mis = s_t[prow] != a.draft_tok[(size_t)b * K + j];
         float z = __builtin_nanf("");
         bool r = false;
         if (mis) {
-            const size_t row = (size_t)b * R + j + a.feat_offset;
+            const size_t row = (size_t)b * R + (TREE ? (a.feat_offset ? j + 1 : prow) : j + a.feat_offset);
             float acc = dot_part<BF16>((const char *)a.hidden_t + row * a.d_t * es, a.clf_w, a.d_t, lane);
             if (a.d_d > 0)
                 acc += dot_part<BF16>((const char *)a.hidden_d + row * a.d_d * es,
@@ -122,6 +127,28 @@ __global__ __launch_bounds__(TAIL_WAVES * 64) void k_verify_tail(TailArgs a)
     }
     __syncthreads();
 
+    if (TREE) {
+        // depth of every accepted node, in topological order (parents come first); K is small, so one lane
+        // walks the nodes; then the deepest accepted node, lowest index among equals
+        __shared__ int32_t s_depth[MAXK + 1];
+        if (threadIdx.x == 0) {
+            int best = -1, best_depth = 0;
+            for (int j = 0; j < K; ++j) {
+                const int p = min(max(a.parent[(size_t)b * K + j], -1), j - 1);
+                const int pd = p < 0 ? 0 : s_depth[p];
+                const int dj = (!s_rej[j] && (p < 0 || pd > 0)) ? pd + 1 : 0;
+                s_depth[j] = dj;
+                if (dj > best_depth) {
+                    best_depth = dj;
+                    best = j;
+                }
+            }
+            a.out_len[b] = best_depth;
+            a.out_tok[b] = s_t[best + 1];
+            a.out_node[b] = best;
+        }
+        return;
+    }
     if (wave == 0) {
         int n = K;
         for (int base = 0; base < K; base += 64) {
@@ -145,10 +172,13 @@ __global__ __launch_bounds__(TAIL_WAVES * 64) void k_verify_tail(TailArgs a)
 hipError_t verify_tail(const TailArgs &a, hipStream_t s)
 {
     if (a.B <= 0) return hipSuccess;
-    if (a.dtype == 1)
-        hipLaunchKernelGGL(k_verify_tail<true>, dim3(a.B), dim3(TAIL_WAVES * 64), 0, s, a);
-    else
-        hipLaunchKernelGGL(k_verify_tail<false>, dim3(a.B), dim3(TAIL_WAVES * 64), 0, s, a);
+    if (a.parent) {
+        if (a.dtype == 1) hipLaunchKernelGGL((k_verify_tail<true, true>), dim3(a.B), dim3(TAIL_WAVES * 64), 0, s, a);
+        else hipLaunchKernelGGL((k_verify_tail<false, true>), dim3(a.B), dim3(TAIL_WAVES * 64), 0, s, a);
+    } else {
+        if (a.dtype == 1) hipLaunchKernelGGL((k_verify_tail<true, false>), dim3(a.B), dim3(TAIL_WAVES * 64), 0, s, a);
+        else hipLaunchKernelGGL((k_verify_tail<false, false>), dim3(a.B), dim3(TAIL_WAVES * 64), 0, s, a);
+    }
     return hipGetLastError();
 }
 
