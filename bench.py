@@ -21,9 +21,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
 RIDGE = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # flop per byte
 
 
-def algorithmic(w, nblocks_bytes=0):
+def algorithmic(w, w_elem_bytes=None):
     """Bytes and flops of one LM-head launch: W_lm and hidden_t read once, logits never stored."""
-    byts = w.V * w.d_t * w.elem_bytes + w.M * w.d_t * w.elem_bytes
+    byts = w.V * w.d_t * (w_elem_bytes or w.elem_bytes) + w.M * w.d_t * w.elem_bytes
     flops = 2.0 * w.M * w.V * w.d_t
     return byts, flops
 
@@ -41,6 +41,9 @@ def main():
                          "top-K lossy baseline on the same LM-head pass; sample: the judge-augmented step with "
                          "Gumbel-max sampled target tokens")
     ap.add_argument("--inv-temperature", type=float, default=1.0)
+    ap.add_argument("--w-dtype", choices=["same", "fp8"], default="same",
+                    help="fp8: W_lm stored as OCP FP8 E4M3 (streaming regime at d_t = 4096 only); not the metric's "
+                         "configuration, which is bf16")
     ap.add_argument("--top-k", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -73,7 +76,13 @@ def main():
 
     # ---- inputs (seeded, synthetic), uploaded once
     ht, hd, W, cw = wl.hidden_t(w, seed), wl.hidden_d(w, seed), wl.w_lm(w, seed), wl.clf_w(w, seed)
-    d_ht, d_hd, d_W, d_cw = (aj.device_tensor(a) for a in (ht, hd, W, cw))
+    fp8 = args.w_dtype == "fp8"
+    w_dtype = aj.AJ_W_FP8_E4M3 if fp8 else aj.AJ_W_SAME
+    W_dev = W
+    if fp8:
+        W_dev, _ = wl.w_lm_fp8(w, seed)
+        W = wl.fp8_e4m3_to_bf16_bits(W_dev)         # the same values, for the CPU baseline
+    d_ht, d_hd, d_W, d_cw = (aj.device_tensor(a) for a in (ht, hd, W_dev, cw))
     out_len = torch.zeros(w.B, dtype=torch.int32, device="cuda")
     out_tok = torch.zeros(w.B, dtype=torch.int32, device="cuda")
     topk = args.mode == "topk"
@@ -83,8 +92,8 @@ def main():
         keys = np.random.default_rng(seed).integers(0, 2**63, size=(w.B, w.K + 1), dtype=np.int64)
         d_key = torch.from_numpy(keys).cuda()
     extra = aj.AJ_FLAG_TOPK if topk else 0
-    h = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, w.dtype_code, 1, extra, args.kernel)
-    hp = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, w.dtype_code, 1, aj.AJ_FLAG_PROFILE | extra, args.kernel)
+    h = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, w.dtype_code, 1, extra, args.kernel, w_dtype)
+    hp = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, w.dtype_code, 1, aj.AJ_FLAG_PROFILE | extra, args.kernel, w_dtype)
     # draft tokens follow the workload recipe relative to the target's greedy tokens; those come
     # from a first (untimed) call of the library itself, with a placeholder draft
     d_draft = torch.zeros((w.B, w.K), dtype=torch.int32, device="cuda")
@@ -130,7 +139,7 @@ def main():
     k1_ms = sum(k1) / len(k1)
     kernel_name = aj.aj_kernel_name(h)
 
-    byts, flops = algorithmic(w)
+    byts, flops = algorithmic(w, 1 if fp8 else None)
     intensity = flops / byts
     if intensity < RIDGE:
         roof = dict(bound="hbm", achieved=byts / (k1_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
@@ -160,6 +169,7 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "K": w.K, "d_t": w.d_t, "d_d": w.d_d, "V": w.V,
                    "verify_rows": w.M, "tau": w.tau, "p_match": w.p_match, "seed": seed,
+                   **({"w_dtype": "fp8_e4m3"} if fp8 else {}),
                    **({"mode": "topk", "top_k": args.top_k} if topk else {}),
                    **({"mode": "sample", "inv_temperature": args.inv_temperature} if sample else {})},
         "verify_rows_per_s": w.M / (ms_per_step * 1e-3),

@@ -65,6 +65,8 @@ enum {
     AJ_FLAG_TOPK = 4     /* also allocate the workspace of aj_verify_topk */
 };
 
+enum { AJ_W_SAME = 0, AJ_W_FP8_E4M3 = 1 };
+
 /* LM-head kernel choice; AJ_KERNEL_AUTO picks by shape. The others force one for tests/benchmarks. */
 enum { AJ_KERNEL_AUTO = 0, AJ_KERNEL_TILE = 1, AJ_KERNEL_STREAM = 2, AJ_KERNEL_BIG = 3, AJ_KERNEL_TALL = 4,
        AJ_KERNEL_PAIR = 5, AJ_KERNEL_PAIR9 = 6 };
@@ -79,6 +81,12 @@ typedef struct {
     int32_t feat_offset; /* 1 (default) or 0: the judge reads verify row j + feat_offset */
     int32_t flags;       /* AJ_FLAG_* */
     int32_t kernel;      /* AJ_KERNEL_* */
+    int32_t w_dtype;     /* storage of W_lm: AJ_W_SAME (0) = `dtype`; AJ_W_FP8_E4M3 = OCP FP8 E4M3 bytes [V][d_t],
+                            widened exactly to bf16 in registers (the 405B run of Section 4 serves the LM head in
+                            FP8); needs dtype = AJ_BF16, B*(K+1) <= 32 and d_t = 4096 (AJ_EINVAL otherwise) and is
+                            not available to aj_verify_topk.  A per-tensor scale of the FP8 weights is the caller's
+                            business: no step of the path depends on the scale of the logits except the
+                            temperature of aj_verify_sampled, into which it can be folded. */
 } aj_config;
 
 /* Validate cfg, allocate the workspace on the current device. *out is NULL on failure. */

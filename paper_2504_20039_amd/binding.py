@@ -16,6 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libaj.so")
 
 AJ_F32, AJ_BF16 = 0, 1
 AJ_FLAG_DEBUG, AJ_FLAG_PROFILE, AJ_FLAG_TOPK = 1, 2, 4
+AJ_W_SAME, AJ_W_FP8_E4M3 = 0, 1
 AJ_KERNEL_AUTO, AJ_KERNEL_TILE, AJ_KERNEL_STREAM, AJ_KERNEL_BIG, AJ_KERNEL_TALL, AJ_KERNEL_PAIR, AJ_KERNEL_PAIR9 = 0, 1, 2, 3, 4, 5, 6
 
 SYMBOLS = ["aj_create", "aj_verify", "aj_verify_sampled", "aj_verify_tree", "aj_verify_topk", "aj_debug_copy_rank", "aj_destroy", "aj_debug_ptrs", "aj_debug_copy", "aj_debug_logits",
@@ -30,7 +31,7 @@ class AjError(RuntimeError):
 
 class _Config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("B", "K", "d_t", "d_d", "V", "dtype", "feat_offset", "flags", "kernel")]
+                ("B", "K", "d_t", "d_d", "V", "dtype", "feat_offset", "flags", "kernel", "w_dtype")]
 
 
 _lib = None
@@ -116,8 +117,8 @@ def _stream(stream):
     return stream.cuda_stream
 
 
-def aj_create(B, K, d_t, d_d, V, dtype=AJ_BF16, feat_offset=1, flags=0, kernel=AJ_KERNEL_AUTO):
-    cfg = _Config(B, K, d_t, d_d, V, dtype, feat_offset, flags, kernel)
+def aj_create(B, K, d_t, d_d, V, dtype=AJ_BF16, feat_offset=1, flags=0, kernel=AJ_KERNEL_AUTO, w_dtype=AJ_W_SAME):
+    cfg = _Config(B, K, d_t, d_d, V, dtype, feat_offset, flags, kernel, w_dtype)
     h = ctypes.c_void_p()
     rc = load_library().aj_create(ctypes.byref(cfg), ctypes.byref(h))
     if rc != 0:

@@ -12,6 +12,7 @@ struct aj_handle {
     int M;
     int variant;   // AJ_KERNEL_* actually used (for bf16), or -1 for the fp32 kernel
     bool stream16; // AJ_KERNEL_STREAM served by the 16-row-tile kernel
+    bool fp8w;     // W_lm stored as FP8 E4M3 (16-row-tile kernel only)
     int nblocks;   // partials per verify row
     int device;
     int num_cus;
@@ -97,7 +98,22 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
         delete h;
         return hip_fail(e);
     }
-    if (c.dtype == AJ_F32) {
+    if (c.w_dtype != AJ_W_SAME && c.w_dtype != AJ_W_FP8_E4M3) {
+        delete h;
+        return AJ_EINVAL;
+    }
+    if (c.w_dtype == AJ_W_FP8_E4M3) {
+        // FP8 weights: the W_lm-streaming kernel only, and no top-K baseline (its pre-pass reads W_lm rows)
+        if (c.dtype != AJ_BF16 || (c.flags & AJ_FLAG_TOPK) || (c.kernel != AJ_KERNEL_AUTO && c.kernel != AJ_KERNEL_STREAM) ||
+            (h->M > 0 && !lm_head_stream16_fp8w_supports(h->M, c.V, c.d_t))) {
+            delete h;
+            return AJ_EINVAL;
+        }
+        h->variant = AJ_KERNEL_STREAM;
+        h->stream16 = true;
+        h->fp8w = true;
+        h->nblocks = lm_head_stream16_blocks(c.V, h->num_cus);
+    } else if (c.dtype == AJ_F32) {
         if (c.kernel != AJ_KERNEL_AUTO) {
             delete h;
             return AJ_EINVAL;
@@ -215,6 +231,7 @@ static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void 
     a.inv_temp = inv_temp;
     if (h->variant < 0) return lm_head_f32(a, s);
     if (h->variant == AJ_KERNEL_TILE) return lm_head_tile_bf16(a, s);
+    if (h->fp8w) return lm_head_stream16_fp8w(a, h->num_cus, s);
     if (h->stream16) return lm_head_stream16_bf16(a, h->num_cus, s);
     if (h->variant == AJ_KERNEL_PAIR) return lm_head_pair_bf16(a, h->num_cus, s);
     if (h->variant == AJ_KERNEL_PAIR9) return lm_head_pair9_bf16(a, h->num_cus, s);
@@ -417,7 +434,8 @@ extern "C" const char *aj_kernel_name(const aj_handle *h)
     switch (h->variant) {
         case -1: return "lm_head_f32";
         case AJ_KERNEL_TILE: return "lm_head_tile_bf16";
-        case AJ_KERNEL_STREAM: return h->stream16 ? "lm_head_stream16_bf16" : "lm_head_stream_bf16";
+        case AJ_KERNEL_STREAM:
+            return h->fp8w ? "lm_head_stream16_fp8w" : h->stream16 ? "lm_head_stream16_bf16" : "lm_head_stream_bf16";
         case AJ_KERNEL_BIG: return "lm_head_big_bf16";
         case AJ_KERNEL_TALL: return "lm_head_tall_bf16";
         case AJ_KERNEL_PAIR: return "lm_head_pair_bf16";

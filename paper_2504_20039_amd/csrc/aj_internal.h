@@ -84,6 +84,9 @@ hipError_t lm_head_mfma_bf16(int variant, const LmHeadArgs &a, int num_cus, hipS
 bool lm_head_stream16_supports(int M, int V, int d);
 int lm_head_stream16_blocks(int V, int num_cus);
 hipError_t lm_head_stream16_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s);
+// the same kernel with W_lm stored as OCP FP8 E4M3 (hidden_t stays bf16): M <= 32, d_t = 4096
+bool lm_head_stream16_fp8w_supports(int M, int V, int d);
+hipError_t lm_head_stream16_fp8w(const LmHeadArgs &a, int num_cus, hipStream_t s);
 
 // 256 x 256 tiles with paired 64-byte half loads (whole 128-byte lines per request pair); d_t % 256 == 0
 bool lm_head_pair_supports(int M, int V, int d);

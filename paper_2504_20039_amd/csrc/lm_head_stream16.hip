@@ -19,6 +19,10 @@
 //     barriers of this exchange are the only ones of a tile.  Lane l holds verify row l % 16 and
 //     vocabulary row 4*(l/16) + r of the tile: ascending over a workgroup's tiles, so strict > keeps the
 //     lowest index; the 4 waves of a row block are merged once, at the end.
+//   * FP8W: W_lm stored as OCP FP8 E4M3 (one byte per element, d_t = 4096): half the bytes to stream.  A
+//     stage is still 16 rows x 512 B, now 512 k elements = 16 k steps; a lane reads its 8 k elements as 8
+//     bytes and widens them exactly to bf16 (v_cvt_pk_f32_fp8, then the upper halves of the floats: E4M3 has
+//     4 significant bits), so the MFMAs and every value they see are those of the bf16 path.
 #include "../../include/aj.h"
 #include "aj_internal.h"
 #include "lds_pipeline.h"
@@ -33,10 +37,22 @@ constexpr int S16_SEG = 512;                    // bytes of each row per stage (
 constexpr int S16_STAGE = S16_ROWS * S16_SEG;   // 8 KB = eight 1 KB loads
 constexpr int S16_LOADS = S16_STAGE / 1024;
 
-template <int NST, bool DUMP, bool TOPK, bool SAMPLE>   // NST stages per tile and wave: d_t = NST * 2048
+// 8 OCP FP8 E4M3 values -> 8 bf16, exactly (E4M3 has 4 significant bits and a narrower exponent range)
+__device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint2 raw)
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw.x, true);
+    const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw.y, false), e = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw.y, true);
+    auto pack = [](float lo, float hi) { return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xffff0000u); };
+    u32x4 w = {pack(a[0], a[1]), pack(b[0], b[1]), pack(c[0], c[1]), pack(e[0], e[1])};
+    return __builtin_bit_cast(bf16x8, w);
+}
+
+template <int NST, bool DUMP, bool TOPK, bool SAMPLE, bool FP8W>   // NST stages per tile and wave: d_t = NST * 2048 (4096 with FP8W)
 __global__ __launch_bounds__(S16_WAVES * 64) void k_lm_head_stream16(LmHeadArgs a, int ntiles)
 {
-    constexpr int KSTEPS = 8;                   // k steps of 32 per stage
+    constexpr int KSTEPS = FP8W ? 16 : 8;       // k steps of 32 per stage (512 B of a row)
+    static_assert(!FP8W || NST == 1, "FP8 W_lm: one 512-byte stage per wave and tile");
     __shared__ __attribute__((aligned(1024))) char lds[S16_WAVES * 2 * S16_STAGE];   // per wave: 2 stage buffers
     __shared__ float redk[S16_WAVES * 8 * 64];  // partial logit blocks: [source wave][register][lane]
     __shared__ Best fin[32 * 4];                // final merge of the 4 waves of a row block
@@ -45,8 +61,9 @@ __global__ __launch_bounds__(S16_WAVES * 64) void k_lm_head_stream16(LmHeadArgs 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l16 = lane & 15, q4 = lane >> 4;
     const char *W = (const char *)a.W, *H = (const char *)a.H;
-    const uint32_t rowbytes = (uint32_t)a.d * 2u;
-    const uint32_t kslice = (uint32_t)wave * (NST * S16_SEG);      // byte offset of this wave's k range in a row
+    const uint32_t rowbytes = (uint32_t)a.d * (FP8W ? 1u : 2u);    // of W_lm
+    const uint32_t kslice = (uint32_t)wave * (NST * S16_SEG);      // byte offset of this wave's k range in a W_lm row
+    const uint32_t hslice = kslice * (FP8W ? 2u : 1u);             // ... in a hidden_t row (always bf16)
     const uint32_t lds_mine = lds_offset_of(lds) + wave * (2 * S16_STAGE);
     const char *lds_rd = lds + wave * (2 * S16_STAGE);
 
@@ -74,7 +91,7 @@ __global__ __launch_bounds__(S16_WAVES * 64) void k_lm_head_stream16(LmHeadArgs 
     bf16x8 hf[NST * KSTEPS][2];
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
-        const char *hrow = H + (size_t)min(b * 16 + l16, a.M - 1) * rowbytes + kslice;
+        const char *hrow = H + (size_t)min(b * 16 + l16, a.M - 1) * ((size_t)a.d * 2) + hslice;
 #pragma unroll
         for (int t = 0; t < NST * KSTEPS; ++t) hf[t][b] = *(const bf16x8 *)(hrow + (t * 32 + q4 * 8) * 2);
     }
@@ -130,7 +147,14 @@ __global__ __launch_bounds__(S16_WAVES * 64) void k_lm_head_stream16(LmHeadArgs 
             const char *buf = lds_rd + cur * S16_STAGE;
 #pragma unroll
             for (int t = 0; t < KSTEPS; ++t) {
-                const bf16x8 fa = *(const bf16x8 *)(buf + a_base + (((4 * t + q4) ^ l16) * 16));
+                bf16x8 fa;
+                if (FP8W) {
+                    // 8 k elements = 8 bytes: 16-byte chunk 2t + q4/2 of the row (swizzled), its half q4 % 2
+                    const uint2 raw = *(const uint2 *)(buf + a_base + (((2 * t + (q4 >> 1)) ^ l16) * 16) + (q4 & 1) * 8);
+                    fa = fp8x8_to_bf16x8(raw);
+                } else {
+                    fa = *(const bf16x8 *)(buf + a_base + (((4 * t + q4) ^ l16) * 16));
+                }
                 acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, hf[st * KSTEPS + t][0], acc[0], 0, 0, 0);
                 acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, hf[st * KSTEPS + t][1], acc[1], 0, 0, 0);
             }
@@ -194,7 +218,7 @@ __global__ __launch_bounds__(S16_WAVES * 64) void k_lm_head_stream16(LmHeadArgs 
     }
 }
 
-template <int NST>
+template <int NST, bool FP8W>
 hipError_t launch16(const LmHeadArgs &a, int num_cus, hipStream_t s)
 {
     const int ntiles = (a.V + S16_ROWS - 1) / S16_ROWS;
@@ -202,13 +226,13 @@ hipError_t launch16(const LmHeadArgs &a, int num_cus, hipStream_t s)
     // the top-K baseline's counting and the sampling noise are separate instantiations: the greedy judge path
     // pays nothing for them
     if (a.dump)
-        hipLaunchKernelGGL((k_lm_head_stream16<NST, true, false, false>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
+        hipLaunchKernelGGL((k_lm_head_stream16<NST, true, false, false, FP8W>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
     else if (a.thr)
-        hipLaunchKernelGGL((k_lm_head_stream16<NST, false, true, false>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
+        hipLaunchKernelGGL((k_lm_head_stream16<NST, false, true, false, FP8W>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
     else if (a.key)
-        hipLaunchKernelGGL((k_lm_head_stream16<NST, false, false, true>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
+        hipLaunchKernelGGL((k_lm_head_stream16<NST, false, false, true, FP8W>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
     else
-        hipLaunchKernelGGL((k_lm_head_stream16<NST, false, false, false>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
+        hipLaunchKernelGGL((k_lm_head_stream16<NST, false, false, false, FP8W>), dim3(grid), dim3(S16_WAVES * 64), 0, s, a, ntiles);
     return hipGetLastError();
 }
 
@@ -226,7 +250,19 @@ int lm_head_stream16_blocks(int V, int num_cus) { return persistent_grid(num_cus
 hipError_t lm_head_stream16_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s)
 {
     if (a.M <= 0) return hipSuccess;
-    return a.d == 4096 ? launch16<2>(a, num_cus, s) : launch16<1>(a, num_cus, s);
+    return a.d == 4096 ? launch16<2, false>(a, num_cus, s) : launch16<1, false>(a, num_cus, s);
+}
+
+// W_lm in OCP FP8 E4M3, hidden_t in bf16: M <= 32 and d_t = 4096 only
+bool lm_head_stream16_fp8w_supports(int M, int V, int d)
+{
+    return M > 0 && M <= 32 && V > 0 && d == 4096 && (uint64_t)V * d < (1ull << 32) && V < (1 << 24);
+}
+
+hipError_t lm_head_stream16_fp8w(const LmHeadArgs &a, int num_cus, hipStream_t s)
+{
+    if (a.M <= 0) return hipSuccess;
+    return launch16<1, true>(a, num_cus, s);
 }
 
 }  // namespace aj

@@ -78,18 +78,20 @@ def oracle_greedy(x, windows=None):
     return t, m1, m2
 
 
-def run_gpu(x, draft, tau, feat_offset=1, kernel=0, clf_b=None, flags=None, repeat=1, sampled=None):
+def run_gpu(x, draft, tau, feat_offset=1, kernel=0, clf_b=None, flags=None, repeat=1, sampled=None, w8=None):
     """One aj_verify (or, with sampled = (inv_temperature, row_key [B][K+1] uint64), aj_verify_sampled) through the
-    C ABI; returns dict of host arrays."""
+    C ABI; returns dict of host arrays.  w8: W_lm as FP8 E4M3 bytes (x.W then holds the same values as bf16 bits
+    for the oracle)."""
     import torch
     import paper_2504_20039_amd as aj
     w = x.w
     clf_b = w.clf_b if clf_b is None else clf_b
     flags = aj.AJ_FLAG_DEBUG if flags is None else flags
-    dev = [aj.device_tensor(a) for a in (x.ht, x.hd, x.W, np.ascontiguousarray(draft, np.int32), x.cw)]
+    dev = [aj.device_tensor(a) for a in (x.ht, x.hd, x.W if w8 is None else w8, np.ascontiguousarray(draft, np.int32), x.cw)]
     out_len = torch.full((max(w.B, 1),), -7, dtype=torch.int32, device="cuda")
     out_tok = torch.full((max(w.B, 1),), -7, dtype=torch.int32, device="cuda")
-    h = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, w.dtype_code, feat_offset, flags, kernel)
+    h = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, w.dtype_code, feat_offset, flags, kernel,
+                     aj.AJ_W_SAME if w8 is None else aj.AJ_W_FP8_E4M3)
     d_key = torch.from_numpy(np.ascontiguousarray(sampled[1], np.uint64).view(np.int64)).cuda() if sampled else None
     try:
         name = aj.aj_kernel_name(h)

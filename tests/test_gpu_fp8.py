@@ -1,0 +1,76 @@
+"""GPU parity with W_lm stored as OCP FP8 E4M3 (the FP8 LM head of the paper's 405B run, Section 4) through the C
+ABI.  The kernel widens the bytes exactly to bf16, so the oracle is fed the decoded weights as bf16 bits and the
+bars are those of the bf16 path (products exact, fp32 accumulation order the only difference)."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from parity import compare, make_inputs, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def fp8_case(w, seed, tau=None, repeat=1, sampled=None):
+    x = make_inputs(w, seed)
+    w8, scale = wl.w_lm_fp8(w, seed)
+    x.W = wl.fp8_e4m3_to_bf16_bits(w8)              # what the kernel computes with, exactly
+    greedy = oracle.greedy_rows(x.ht, x.W) if sampled is None else \
+        oracle.sampled_rows(x.ht, x.W, sampled[0], sampled[1].reshape(-1))
+    draft = wl.draft_tokens(w, seed, greedy[0])
+    tau = w.tau if tau is None else tau
+    gpu = run_gpu(x, draft, tau, repeat=repeat, w8=w8, sampled=sampled)
+    scores_row = None
+    if sampled is not None:
+        keys = sampled[1].reshape(-1)
+
+        def scores_row(r):
+            return oracle.logits_row(x.ht[r], x.W) * sampled[0] + np.array([oracle.gumbel(int(keys[r]), v) for v in range(w.V)])
+    rep = compare(x, draft, tau, greedy, gpu, scores_row=scores_row)
+    assert gpu["kernel"] == "lm_head_stream16_fp8w"
+    return rep, x, w8, gpu
+
+
+@pytest.mark.parametrize("shape", [
+    dict(B=1, K=16, V=5003),           # ragged vocabulary
+    dict(B=2, K=15, V=9000),           # all 32 rows
+    dict(B=1, K=4, V=40),              # fewer tiles than workgroups
+    dict(B=3, K=7, V=70001),           # more tiles than workgroups: several per workgroup
+])
+def test_fp8_weights(shape):
+    w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="fp8", p_match=0.6, **shape)
+    for tau in (0.0, 0.5, 1.0):
+        rep, x, w8, gpu = fp8_case(w, 13, tau=tau, repeat=2)
+        assert rep["maxlogit_relerr"] < 1e-4
+    # all logits through the same kernel
+    import torch
+    import paper_2504_20039_amd as aj
+    h = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, aj.AJ_BF16, 1, 0, 0, aj.AJ_W_FP8_E4M3)
+    logits = torch.empty((w.M, w.V), dtype=torch.float32, device="cuda")
+    aj.aj_debug_logits(h, aj.device_tensor(x.ht), aj.device_tensor(w8), logits)
+    torch.cuda.synchronize()
+    aj.aj_destroy(h)
+    ref = wl.widen(x.ht) @ wl.widen(x.W).T
+    assert np.abs(logits.cpu().numpy() - ref).max() <= 1e-4 * np.abs(ref).max()
+
+
+def test_fp8_sampling_and_full_size():
+    w = wl.WORKLOADS["8b_b1_k16"]
+    rep, x, w8, gpu = fp8_case(w, wl.DEFAULT_SEED, repeat=2)
+    print(rep)
+    keys = np.random.default_rng(2).integers(0, 2**63, size=(w.B, w.K + 1), dtype=np.uint64)
+    # the weights are scaled by 1/scale: fold the scale into the temperature so that T = 1 in the original units
+    _, scale = wl.w_lm_fp8(w, wl.DEFAULT_SEED)
+    fp8_case(w, wl.DEFAULT_SEED, sampled=(scale, keys))
+
+
+def test_fp8_refusals():
+    import paper_2504_20039_amd as aj
+    ok = dict(B=1, K=16, d_t=4096, d_d=64, V=1000)
+    for bad in (dict(d_t=2048), dict(B=3), dict(dtype=aj.AJ_F32), dict(flags=aj.AJ_FLAG_TOPK), dict(kernel=aj.AJ_KERNEL_PAIR),
+                dict(w_dtype=7)):
+        a = dict(ok, dtype=aj.AJ_BF16, flags=0, kernel=0, w_dtype=aj.AJ_W_FP8_E4M3)
+        a.update(bad)
+        with pytest.raises(aj.AjError) as e:
+            aj.aj_create(a["B"], a["K"], a["d_t"], a["d_d"], a["V"], a["dtype"], 1, a["flags"], a["kernel"], a["w_dtype"])
+        assert e.value.status == -1, bad

@@ -168,6 +168,32 @@ def w_lm(w: Workload, seed: int, row0: int = 0, rows: int | None = None) -> np.n
     return normal_rows(seed, TID_W_LM, row0, rows, w.d_t, 0.02, False, w.dtype)
 
 
+# OCP FP8 E4M3 storage of W_lm (the FP8 LM head of the paper's 405B run, Section 4): encode / decode are
+# the library's (torch CPU); the decode is exact, so the oracle can be fed the decoded values as bf16 bits.
+
+def fp8_e4m3_encode(x: np.ndarray) -> np.ndarray:
+    """float array -> E4M3 bytes (uint8), round to nearest even."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x, np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+
+
+def fp8_e4m3_to_bf16_bits(b: np.ndarray) -> np.ndarray:
+    """E4M3 bytes -> the same values as bf16 bits (uint16); exact, E4M3 has 4 significant bits."""
+    import torch
+    f = torch.from_numpy(np.ascontiguousarray(b, np.uint8)).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    u = f.view(np.uint32)
+    assert np.all((u & 0xFFFF) == 0)
+    return (u >> 16).astype(np.uint16)
+
+
+def w_lm_fp8(w: Workload, seed: int):
+    """(E4M3 bytes [V, d_t], scale): the bf16 workload's W_lm divided by a per-tensor scale that puts its
+    largest magnitude at 440 (E4M3 tops out at 448), rounded to E4M3."""
+    W = widen(w_lm(w, seed))
+    scale = float(np.abs(W).max() / 440.0)
+    return fp8_e4m3_encode(W / scale), scale
+
+
 def clf_w(w: Workload, seed: int) -> np.ndarray:
     """Judge weights [d_t + d_d], N(0, 1/(d_t+d_d)); target part first."""
     return normal_rows(seed, TID_CLF_W, 0, 1, w.D, 1.0 / math.sqrt(w.D), False, w.dtype)[0]
