@@ -123,7 +123,10 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
     } else {
         int v = c.kernel;
         if (v == AJ_KERNEL_AUTO) {
-            // W_lm-streaming regime while one 32-row block holds every verify row.  Above that, the large-tile
+            // W_lm-streaming kernels up to 128 verify rows: the 16-row-tile kernel with hidden_t in registers
+            // (<= 32 rows, d_t = 2048 or 4096), else 128-vocabulary tiles of 32, 64 or 128 rows with a running
+            // maximum (5.7 TB/s at 34..64 rows, 4.8 at 65..128, against 4.4 of a padded 256-row tile).  Above
+            // that, the large-tile
             // kernel with the lowest cost = padded row count x a per-row factor measured on one device against
             // the 256-row whole-line kernel (PAIR = 1): its 288-row variant 1.06, the 256-row kernel with
             // 64-byte pieces 1.10, the 8-wave 288/320-row kernel 1.15.  Padded rows are wasted MFMA work, and a

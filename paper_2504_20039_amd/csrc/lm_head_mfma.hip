@@ -83,7 +83,9 @@ struct Shape {
     static_assert(!PIPE || PIPE_VMCNT <= 63, "vmcnt range");
 };
 
-using StreamShape = Shape<1, 1, 4, 1, 1, 128, 3, true>;            // any d_t % 128 == 0
+using StreamShape = Shape<1, 1, 4, 1, 1, 128, 3, true>;            // up to 32 verify rows; any d_t % 128 == 0
+using Stream64Shape = Shape<1, 2, 4, 1, 1, 128, 3, true>;          // 33..64 rows: 128 x 64 tile, same pipeline
+using Stream128Shape = Shape<1, 4, 4, 1, 1, 64, 4, true>;          // 65..128 rows: 128 x 128 tile, BK = 64, 4 stages
 using BigShape = Shape<4, 4, 2, 2, 1, 32, 4, false, true>;
 using TallShape = Shape<2, 5, 4, 2, 1, 64, 2, false>;                 // 256 x 320, 8 waves: 289..320 verify rows in ONE row tile
 using Tall288Shape = Shape<2, 5, 4, 2, 1, 64, 2, false, false, 1>;   // 256 x 288 (wave rows of 5 + 4 blocks)
@@ -526,7 +528,7 @@ bool lm_head_mfma_supports(int variant, int M, int V, int d)
     if (V >= (1 << 24) || M >= (1 << 24) || d * 2 >= (1 << 24)) return false;
     // whole k stages only, and at least as many as the pipeline runs ahead
     if (variant == AJ_KERNEL_STREAM)
-        return d % StreamShape::BK == 0 && d / StreamShape::BK >= StreamShape::NS - 1 && M <= StreamShape::BM;
+        return d % StreamShape::BK == 0 && d / StreamShape::BK >= Stream128Shape::NS - 1 && M <= Stream128Shape::BM;
     if (variant == AJ_KERNEL_BIG) return d % BigShape::BK == 0 && d / BigShape::BK >= BigShape::NS - 1;
     if (variant == AJ_KERNEL_TALL)
         return d % TallShape::BK == 0 && d / TallShape::BK >= TallShape::NS - 1;
@@ -539,14 +541,16 @@ int lm_head_mfma_padded_rows(int variant, int M)
     auto pad = [M](int bm) { return (M + bm - 1) / bm * bm; };
     if (variant == AJ_KERNEL_TALL) return pad(Tall288Shape::BM) < pad(TallShape::BM) ? pad(Tall288Shape::BM) : pad(TallShape::BM);
     if (variant == AJ_KERNEL_BIG) return pad(BigShape::BM);
-    return pad(StreamShape::BM);
+    return M <= StreamShape::BM ? StreamShape::BM : M <= Stream64Shape::BM ? Stream64Shape::BM : pad(Stream128Shape::BM);
 }
 
 hipError_t lm_head_mfma_bf16(int variant, const LmHeadArgs &a, int num_cus, hipStream_t s)
 {
     if (a.M <= 0) return hipSuccess;
     if (variant == AJ_KERNEL_STREAM)
-        return launch<StreamShape>(a, num_cus, 1, s);
+        return a.M <= StreamShape::BM     ? launch<StreamShape>(a, num_cus, 1, s)
+               : a.M <= Stream64Shape::BM ? launch<Stream64Shape>(a, num_cus, 1, s)
+                                          : launch<Stream128Shape>(a, num_cus, 1, s);
     if (variant == AJ_KERNEL_TALL) {
         // 288- or 320-row tiles, whichever pads the row count less (ties: the taller one, fewer tiles)
         const int pad288 = (a.M + Tall288Shape::BM - 1) / Tall288Shape::BM * Tall288Shape::BM;

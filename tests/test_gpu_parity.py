@@ -56,6 +56,8 @@ def test_tiny_f32_workload_with_all_logits():
     dict(B=2, K=15, d_t=2048, d_d=128, V=9000),        # ... at d_t = 2048, all 32 rows
     dict(B=1, K=4, d_t=4096, d_d=64, V=40),            # ... fewer tiles than workgroups
     dict(B=9, K=31, d_t=512, d_d=64, V=60000),         # 2 x 235 large tiles: workgroups with two tiles and with one
+    dict(B=4, K=24, d_t=512, d_d=64, V=3000),          # M=100: the 128-row streaming tile
+    dict(B=2, K=31, d_t=8192, d_d=64, V=1500),         # M=64 exactly at the 70B hidden size
 ])
 def test_bf16_shapes_all_kernels(kernel, shape):
     import torch
@@ -270,11 +272,11 @@ def test_profile_events_and_kernel_names():
     with pytest.raises(aj.AjError):
         aj.aj_profile_read(plain)
     aj.aj_destroy(plain)
-    for M_B, d_t, name in ((8, 4096, "lm_head_pair_bf16"), (8, 4096 + 64, "lm_head_big_bf16"), (4, 4096, "lm_head_pair_bf16"),
+    for M_B, d_t, name in ((8, 4096, "lm_head_pair_bf16"), (8, 4096 + 64, "lm_head_big_bf16"), (4, 4096, "lm_head_stream_bf16"), (5, 4096, "lm_head_pair_bf16"),
                            (4, 4096 + 8, "lm_head_tile_bf16"), (9, 4096, "lm_head_pair9_bf16"), (10, 4096, "lm_head_tall_bf16"),
                            (33, 4096, "lm_head_pair9_bf16"), (33, 4096 + 64, "lm_head_tall_bf16"),
                            (260, 4096, "lm_head_pair_bf16")):
-        hh = aj.aj_create(M_B, 31, d_t, 64, 4096, aj.AJ_BF16)     # 256, 256, 128, 128, 288, 320, 1056, 1056, 8320 verify rows
+        hh = aj.aj_create(M_B, 31, d_t, 64, 4096, aj.AJ_BF16)     # 256, 256, 128, 160, 128, 288, 320, 1056, 1056, 8320 verify rows
         assert aj.aj_kernel_name(hh) == name, (M_B, aj.aj_kernel_name(hh))
         aj.aj_destroy(hh)
 

@@ -104,6 +104,7 @@ def test_tiny_f32():
     dict(B=3, K=16, d_t=1024, d_d=64, V=2500),         # general 128x128 kernel
     dict(B=9, K=31, d_t=512, d_d=64, V=3001),          # M=288: 256-row kernels (2 row tiles) and the 8-wave one
     dict(B=20, K=31, d_t=256, d_d=64, V=1100),         # M=640
+    dict(B=4, K=24, d_t=512, d_d=64, V=3000),          # M=100: the 128-row streaming tile
 ])
 def test_bf16_shapes_all_kernels(kernel, shape):
     import paper_2504_20039_amd as aj
