@@ -26,6 +26,10 @@
  * sigmoid(z) < tau in real arithmetic and makes tau = 0 plain greedy
  * speculative decoding and tau = 1 accept every draft token.
  *
+ * aj_verify is that path.  On the same LM-head pass: aj_verify_sampled (step 2 samples the target's
+ * token with the Gumbel-max trick instead of taking the maximum), aj_verify_tree (the K slots form a
+ * draft tree), aj_verify_topk (the paper's top-K lossy baseline in place of the judge).
+ *
  * Conventions
  *   - All tensor arguments are DEVICE pointers owned by the caller, row-major,
  *     16-byte aligned; clf_b and tau are host scalars.  The library keeps none
