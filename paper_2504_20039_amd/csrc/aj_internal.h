@@ -71,7 +71,7 @@ __device__ __forceinline__ float gumbel_noise(uint32_t klo, uint32_t khi, uint32
 // Number of vocabulary blocks (partials per row) each variant produces for V.
 int lm_head_tile_blocks(int V);
 int lm_head_f32_blocks(int V);
-int lm_head_mfma_blocks(int variant, int V, int d, int num_cus);  // variant: AJ_KERNEL_STREAM / AJ_KERNEL_BIG
+int lm_head_mfma_blocks(int variant, int V, int d, int num_cus);  // variant: AJ_KERNEL_STREAM, _BIG or _TALL
 bool lm_head_mfma_supports(int variant, int M, int V, int d);
 int lm_head_mfma_padded_rows(int variant, int M);
 

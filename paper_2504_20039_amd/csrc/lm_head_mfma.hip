@@ -1,5 +1,5 @@
 // LM head (step 1) fused with the per-vocabulary-block greedy maximum (first half of step 2):
-// the two performance kernels, one template.
+// the general template of the large-tile and streaming-tile kernels.
 //
 //   * persistent workgroups (one per compute unit) walk a list of logit tiles; the k-loop of
 //     all their tiles is ONE software pipeline, so the HBM stream never drains at a tile edge;
@@ -15,13 +15,16 @@
 //     tiles go to the workgroups of one XCD (workgroup id mod 8), so that the 32 compute units
 //     behind one L2 work on a compact block of tiles that share operand panels.
 //
-// Three instantiations:
+// Instantiations:
 //   STREAM  128 vocabulary x 32 verify rows, BK = 128, 3 stages, one running partial per workgroup and
 //           wave column: W_lm-streaming regime (M <= 32) at hidden sizes the register-resident
-//           16-row-tile kernel (lm_head_stream16.hip) does not take.
-//   BIG     256 x 256, 4 waves of 128 x 128, BK = 32, 4 stages, hand-scheduled stage: MFMA-bound regime.
-//   TALL    256 x 320, 8 waves of 64 x 160, BK = 32, 4 stages: 257..320 verify rows in ONE row tile, so
-//           that W_lm is read once and no nearly empty second row tile is computed.
+//           16-row-tile kernel (lm_head_stream16.hip) does not take; the same with 128 x 64 tiles for
+//           33..64 rows and 128 x 128 tiles (BK = 64, 4 stages) for 65..128 rows.
+//   BIG     256 x 256, 4 waves of 128 x 128, BK = 32, 4 stages, hand-scheduled stage: MFMA-bound regime at
+//           hidden sizes lm_head_pair.hip does not take (not a multiple of 256).
+//   TALL    256 x 320 or 256 x 288 (wave rows of 5 + 4 blocks), 8 waves, BK = 64, 2 stages: 289..320 verify
+//           rows in ONE row tile (and 257..288 at hidden sizes lm_head_pair9.hip does not take), so that
+//           W_lm is read once and no nearly empty second row tile is computed.
 #include "../../include/aj.h"
 #include "aj_internal.h"
 #include "lds_pipeline.h"
