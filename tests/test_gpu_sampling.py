@@ -113,3 +113,31 @@ def test_full_size_default_workload():
     rep, x, keys, ref, gpu = sampling_case(w, wl.DEFAULT_SEED, 1.0, repeat=2)
     print(rep)
     assert gpu["kernel"] == "lm_head_stream16_bf16"
+
+
+@pytest.mark.parametrize("name,windows", [("70b_b8_k32", (0, 7)), ("70b_b128_k64", (127,))])
+def test_full_size_sampled_windows(name, windows):
+    """The large workloads in the launch configuration bench.py times: sampled tokens, perturbed maxima and
+    outcomes of a few windows against the oracle (windows are independent), properties on all windows."""
+    w = wl.WORKLOADS[name]
+    seed = wl.DEFAULT_SEED
+    x = make_inputs(w, seed)
+    keys = keys_for(w, 5)
+    R = w.K + 1
+    inv_t = 1.0
+    t = np.full(w.M, -1, np.int32)
+    m1, m2 = np.full(w.M, np.nan), np.full(w.M, np.nan)
+    for b in windows:
+        sl = slice(b * R, (b + 1) * R)
+        t[sl], m1[sl], m2[sl] = oracle.sampled_rows(x.ht[sl], x.W, inv_t, keys[b])
+    draft = wl.draft_tokens(w, seed, t)              # windows without oracle rows get uniform tokens
+    gpu = run_gpu(x, draft, w.tau, sampled=(inv_t, keys))
+
+    def scores_row(r):
+        lg = oracle.logits_row(x.ht[r], x.W) * inv_t
+        return lg + np.array([oracle.gumbel(int(keys.reshape(-1)[r]), v) for v in range(w.V)])
+    rep = compare(x, draft, w.tau, (t, m1, m2), gpu, windows=windows, scores_row=scores_row)
+    print(rep)
+    assert ((gpu["out_len"] >= 0) & (gpu["out_len"] <= w.K)).all()
+    assert np.array_equal(gpu["out_tok"], gpu["t_star"][np.arange(w.B) * R + gpu["out_len"]])
+    assert ((gpu["t_star"] >= 0) & (gpu["t_star"] < w.V)).all()
