@@ -291,3 +291,14 @@ def test_profile_events_and_kernel_names():
 def test_run_to_run_bit_identical(kernel, shape):
     w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="det", p_match=0.5, **shape)
     parity_case(w, 17, kernel=kernel, repeat=10)
+
+
+@pytest.mark.parametrize("d_t", [512, 320, 200])       # whole-line kernels; 64-byte-piece kernels; general kernel only
+@pytest.mark.parametrize("B,K", [(1, 31), (1, 32), (2, 31), (5, 12), (4, 31), (3, 42), (8, 31), (1, 256), (9, 31),
+                                 (17, 16), (10, 31), (3, 106), (16, 31), (19, 26), (18, 31), (1, 576)])
+def test_dispatch_boundaries(B, K, d_t):
+    """Row counts on both sides of every dispatch boundary (32|33, 64|65, 128|129, 256|257, 288|289, 320|321,
+    512|513, 576|577), whatever kernel AUTO picks at each hidden size."""
+    w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="edge", p_match=0.6, B=B, K=K, d_t=d_t, d_d=64, V=1500)
+    rep, x, draft, greedy, gpu = parity_case(w, 29, repeat=2)
+    assert rep["near_thr_windows"] == 0
