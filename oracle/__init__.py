@@ -28,6 +28,9 @@ def build(force: bool = False) -> str:
     if force or (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
+    if force:   # the self-test program (run under sanitizers by the tests) must at least compile
+        selftest = os.path.join(os.path.dirname(_SRC), "selftest.c")
+        subprocess.run(["gcc", "-O1", "-fopenmp", "-Wall", "-c", selftest, "-o", os.devnull], check=True)
     return _LIB
 
 
