@@ -290,7 +290,7 @@ def test_profile_events_and_kernel_names():
 ])
 def test_run_to_run_bit_identical(kernel, shape):
     w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="det", p_match=0.5, **shape)
-    parity_case(w, 17, kernel=kernel, repeat=10)
+    parity_case(w, 17, kernel=kernel, repeat=100)
 
 
 @pytest.mark.parametrize("d_t", [512, 320, 200])       # whole-line kernels; 64-byte-piece kernels; general kernel only
