@@ -35,6 +35,13 @@ def test_gumbel_matches_closed_form_cdf():
     assert abs(np.corrcoef(a[:-1], a[1:])[0, 1]) < 0.03
     assert abs(np.corrcoef(a, b)[0, 1]) < 0.03
     assert stats.kstest(a, lambda t: np.exp(-np.exp(-t))).pvalue > 1e-3
+    # both halves of the 64-bit key matter: keys that differ only in the upper, or only in the lower, 32 bits
+    # give unrelated streams
+    base = 0x0123456789ABCDEF
+    for other in (base ^ (1 << 40), base ^ (1 << 3), base ^ (1 << 63)):
+        c = np.array([oracle.gumbel(base, v) for v in range(5000)])
+        e = np.array([oracle.gumbel(other, v) for v in range(5000)])
+        assert not np.array_equal(c, e) and abs(np.corrcoef(c, e)[0, 1]) < 0.06
 
 
 @pytest.mark.parametrize("inv_t", [1.0, 0.5, 2.5])
