@@ -51,8 +51,8 @@ __device__ __forceinline__ int32_t ranks_before(float val, int32_t v, float th, 
 
 // Sampling mode (Appendix A, "Generalization to sampling": argmax of log-probabilities plus Gumbel noise
 // from a generator seeded by the random state and the context).  Counter-based generator, one 64-bit key
-// per verify row:  h = v * 0x9E3779B1 + lo32(key); h ^= h >> 16; h *= 0x85EBCA6B; h ^= h >> 13;
-// h += hi32(key); h *= 0xC2B2AE35; h ^= h >> 16;  u = ((h >> 9) + 0.5) * 2^-23 (exact in fp32);
+// per verify row:  h = v * 0x9E3779B1 + lo32(key); h ^= h >> 16; h *= 0x85EBCA6B; h ^= hi32(key); h ^= h >> 13;
+// h *= 0xC2B2AE35; h ^= h >> 16; h *= 0x27D4EB2F; h ^= h >> 15;  u = ((h >> 9) + 0.5) * 2^-23 (exact in fp32);
 // noise = -log(-log(u)).  Both logarithms are the accurate ones: the largest noise values, which decide
 // the maximum, come from u within 1e-4 of 1, where a fast log2 has no relative accuracy.
 __device__ __forceinline__ float gumbel_noise(uint32_t klo, uint32_t khi, uint32_t v)
@@ -60,10 +60,12 @@ __device__ __forceinline__ float gumbel_noise(uint32_t klo, uint32_t khi, uint32
     uint32_t h = v * 0x9E3779B1u + klo;
     h ^= h >> 16;
     h *= 0x85EBCA6Bu;
+    h ^= khi;
     h ^= h >> 13;
-    h += khi;
     h *= 0xC2B2AE35u;
     h ^= h >> 16;
+    h *= 0x27D4EB2Fu;
+    h ^= h >> 15;
     const float u = ((float)(h >> 9) + 0.5f) * (1.0f / 8388608.0f);
     return -logf(-logf(u));
 }
