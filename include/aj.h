@@ -142,7 +142,7 @@ int aj_verify_tree(aj_handle *h, const void *hidden_t, const void *hidden_d, con
  *                            the row's context hashes to (the same key gives the same noise)
  *   inv_temperature          1/T >= 0, finite (0: uniformly random tokens; large: greedy decoding)
  * Noise generator (counter-based, any (row, v) on its own), all arithmetic mod 2^32:
- *     h = v * 0x9E3779B1 + lo32(key); h ^= h >> 16; h *= 0x85EBCA6B; h ^= hi32(key);
+ *     h = v * 0x9E3779 + lo32(key); h ^= h >> 16; h *= 0x85EBCA6B; h ^= hi32(key);
  *     h ^= h >> 13; h *= 0xC2B2AE35; h ^= h >> 16; h *= 0x27D4EB2F; h ^= h >> 15;
  *     u = ((h >> 9) + 0.5) * 2^-23;   G = -log(-log(u))
  * aj_debug_* then report y and the perturbed maximum in place of the greedy token and its logit.

@@ -465,7 +465,7 @@ int ajo_verify_topk(int B, int K, int d_t, int V, int dtype, int top_k,
  * The paper names no generator.  This one is counter-based so that every (row, v) can be
  * evaluated independently, and is specified by this text, which the GPU library implements
  * on its own:
- *     h = v * 0x9E3779B1 + lo32(key);  h ^= h >> 16;  h *= 0x85EBCA6B;  h ^= hi32(key);
+ *     h = v * 0x9E3779 + lo32(key);  h ^= h >> 16;  h *= 0x85EBCA6B;  h ^= hi32(key);
  *     h ^= h >> 13;  h *= 0xC2B2AE35;  h ^= h >> 16;  h *= 0x27D4EB2F;  h ^= h >> 15;   (all mod 2^32)
  *     u = ((h >> 9) + 0.5) * 2^-23   in (0,1);      G = -log(-log(u))
  * 23 bits, so that u (an odd multiple of 2^-24 below 1) is exact in fp32 as well as in fp64; the
@@ -473,7 +473,7 @@ int ajo_verify_topk(int B, int K, int d_t, int V, int dtype, int top_k,
  */
 static inline uint32_t ajo_noise_bits(uint64_t key, uint32_t v)
 {
-    uint32_t h = v * 0x9E3779B1u + (uint32_t)(key & 0xffffffffu);
+    uint32_t h = v * 0x9E3779u + (uint32_t)(key & 0xffffffffu);
     h ^= h >> 16;
     h *= 0x85EBCA6Bu;
     h ^= (uint32_t)(key >> 32);

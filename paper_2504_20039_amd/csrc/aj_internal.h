@@ -51,13 +51,15 @@ __device__ __forceinline__ int32_t ranks_before(float val, int32_t v, float th, 
 
 // Sampling mode (Appendix A, "Generalization to sampling": argmax of log-probabilities plus Gumbel noise
 // from a generator seeded by the random state and the context).  Counter-based generator, one 64-bit key
-// per verify row:  h = v * 0x9E3779B1 + lo32(key); h ^= h >> 16; h *= 0x85EBCA6B; h ^= hi32(key); h ^= h >> 13;
+// per verify row:  h = v * 0x9E3779 + lo32(key); h ^= h >> 16; h *= 0x85EBCA6B; h ^= hi32(key); h ^= h >> 13;
 // h *= 0xC2B2AE35; h ^= h >> 16; h *= 0x27D4EB2F; h ^= h >> 15;  u = ((h >> 9) + 0.5) * 2^-23 (exact in fp32);
-// noise = -log(-log(u)).  Both logarithms are the accurate ones: the largest noise values, which decide
-// the maximum, come from u within 1e-4 of 1, where a fast log2 has no relative accuracy.
+// noise = -log(-log(u)).  The largest noise values, which decide the maximum over the vocabulary, come from u
+// within 1e-4 of 1, where a hardware log2 has no relative accuracy: there -log(u) = -log(1 - x), x = 1 - u
+// (exact), is taken from its series; elsewhere, and for the outer logarithm, the fast log2 is accurate to ~1e-7
+// of the result.  
 __device__ __forceinline__ float gumbel_noise(uint32_t klo, uint32_t khi, uint32_t v)
 {
-    uint32_t h = v * 0x9E3779B1u + klo;
+    uint32_t h = __umul24(v, 0x9E3779u) + klo;       // v < 2^24 and a 24-bit constant: a full-rate multiply-add
     h ^= h >> 16;
     h *= 0x85EBCA6Bu;
     h ^= khi;
@@ -67,7 +69,12 @@ __device__ __forceinline__ float gumbel_noise(uint32_t klo, uint32_t khi, uint32
     h *= 0x27D4EB2Fu;
     h ^= h >> 15;
     const float u = ((float)(h >> 9) + 0.5f) * (1.0f / 8388608.0f);
-    return -logf(-logf(u));
+    const float x = 1.0f - u;
+    // -log(1 - x) = x + x^2/2 + x^3/3 + x^4/4 + x^5/5 + ...: below x = 1/16 the omitted terms are < 2e-8 of the sum
+    const float series = x * fmaf(x, fmaf(x, fmaf(x, fmaf(x, 0.2f, 0.25f), 1.0f / 3.0f), 0.5f), 1.0f);
+    // v_log_f32 is log2; its arguments here are never subnormal (u >= 2^-24, -log u >= 5.9e-8)
+    const float e = x < 0.0625f ? series : -0.69314718f * __builtin_amdgcn_logf(u);
+    return -0.69314718f * __builtin_amdgcn_logf(e);
 }
 
 // Number of vocabulary blocks (partials per row) each variant produces for V.
