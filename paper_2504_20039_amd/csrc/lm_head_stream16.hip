@@ -15,8 +15,8 @@
 //   * W_lm is read exactly once, so its loads carry the non-temporal hint (6.2 -> 6.5 TB/s).
 //   * per tile the 8 partial 16x32 logit blocks meet in LDS and every wave adds up one eighth of the block
 //     (one accumulator register index: verify rows 16b..16b+15 x vocabulary rows 4q+r for its (b, r)),
-//     keeping a running (max, lowest index) per lane: no wave does more than the others, and the two
-//     barriers of this exchange are the only ones of a tile.  Lane l holds verify row l % 16 and
+//     keeping a running (max, lowest index) per lane: no wave does more than the others, and the one
+//     barrier of this exchange (its area is double-buffered) is the only one of a tile.  Lane l holds verify row l % 16 and
 //     vocabulary row 4*(l/16) + r of the tile: ascending over a workgroup's tiles, so strict > keeps the
 //     lowest index; the 4 waves of a row block are merged once, at the end.
 //   * FP8W: W_lm stored as OCP FP8 E4M3 (one byte per element, d_t = 4096): half the bytes to stream.  A
@@ -54,7 +54,7 @@ __global__ __launch_bounds__(S16_WAVES * 64) void k_lm_head_stream16(LmHeadArgs 
     constexpr int KSTEPS = FP8W ? 16 : 8;       // k steps of 32 per stage (512 B of a row)
     static_assert(!FP8W || NST == 1, "FP8 W_lm: one 512-byte stage per wave and tile");
     __shared__ __attribute__((aligned(1024))) char lds[S16_WAVES * 2 * S16_STAGE];   // per wave: 2 stage buffers
-    __shared__ float redk[S16_WAVES * 8 * 64];  // partial logit blocks: [source wave][register][lane]
+    __shared__ float redk[2 * S16_WAVES * 7 * 64];   // partial logit blocks: [tile parity][share][source slot][lane]
     __shared__ Best fin[32 * 4];                // final merge of the 4 waves of a row block
     __shared__ int32_t finc[32 * 4];
 
@@ -160,17 +160,23 @@ __global__ __launch_bounds__(S16_WAVES * 64) void k_lm_head_stream16(LmHeadArgs 
             }
         }
 
-        // ---- the 8 partial blocks meet in LDS; wave w adds up register (bsel, rsel) of all of them
+        // ---- the 8 partial blocks meet in LDS; wave w adds up register (bsel, rsel) = share w of all of them.
+        // A wave keeps its own share in registers and writes the 7 others; the exchange area is double-buffered
+        // by tile parity, so ONE barrier per tile suffices: a wave that writes buffer p again (two tiles later) has
+        // passed the barrier in between, which every wave reaches only after its reads of buffer p.
+        float *rk = redk + (step & 1) * (S16_WAVES * 7 * 64);
+        float own = 0.f;
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) redk[((wave * 2 + b) * 4 + r) * 64 + lane] = acc[b][r];
+        for (int s = 0; s < S16_WAVES; ++s) {
+            const float val = acc[s >> 2][s & 3];
+            if (s == wave) own = val;
+            else rk[(s * 7 + (wave < s ? wave : wave - 1)) * 64 + lane] = val;     // share s, slot of source wave
+        }
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         float sum = 0.f;
 #pragma unroll
-        for (int w = 0; w < S16_WAVES; ++w) sum += redk[((w * 2 + bsel) * 4 + rsel) * 64 + lane];
-        // everyone has read before anyone writes the next tile's partials
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        for (int w = 0; w < S16_WAVES; ++w)      // ascending source wave, whichever wave adds
+            sum += w == wave ? own : rk[(wave * 7 + (w < wave ? w : w - 1)) * 64 + lane];
         const int v = T * S16_ROWS + q4 * 4 + rsel;
         if (v < a.V) {
             if (DUMP && myrow < a.M) a.dump[(size_t)myrow * a.V + v] = sum;
