@@ -80,7 +80,7 @@ typedef struct {
     int32_t K;           /* draft tokens per window, 1 <= K <= 1023 */
     int32_t d_t;         /* target hidden size; multiple of 8 (bf16) or 4 (f32) */
     int32_t d_d;         /* draft hidden size; 0 = judge on target states only; same multiples */
-    int32_t V;           /* vocabulary size, >= 1 */
+    int32_t V;           /* vocabulary size, 1 <= V < 2^24 */
     int32_t dtype;       /* aj_dtype of hidden_t, hidden_d, W_lm, clf_w */
     int32_t feat_offset; /* 1 (default) or 0: the judge reads verify row j + feat_offset */
     int32_t flags;       /* AJ_FLAG_* */
@@ -105,7 +105,8 @@ int aj_create(const aj_config *cfg, aj_handle **out);
  *   clf_w     [d_t + d_d]     judge weight, target part first
  *   out_len   [B] int32       accepted draft tokens, in [0, K]
  *   out_tok   [B] int32       emitted token, in [0, V)
- * AJ_EINVAL on null / misaligned pointers or tau outside [0,1]; AJ_EHIP on a launch failure.
+ * AJ_EINVAL on null / misaligned pointers, tau outside [0,1] or NaN, or a non-finite clf_b; AJ_EHIP on a
+ * launch failure.
  */
 int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_d, const void *W_lm,
               const int32_t *draft_tok, const void *clf_w, float clf_b, float tau,

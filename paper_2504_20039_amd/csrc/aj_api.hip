@@ -71,11 +71,10 @@ static void free_all(aj_handle *h)
         }
 }
 
-extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
+// Validate a configuration and choose the LM-head kernel for it on the current device: fills everything of *h
+// that is not a device allocation.  Allocates nothing.
+static int plan_handle(const aj_config &c, aj_handle *h)
 {
-    if (out) *out = nullptr;
-    if (!cfg || !out) return AJ_EINVAL;
-    const aj_config &c = *cfg;
     if (c.dtype != AJ_F32 && c.dtype != AJ_BF16) return AJ_EINVAL;
     const int mult = c.dtype == AJ_BF16 ? 8 : 4;
     if (c.B < 0 || c.K < 1 || c.K > 1023 || c.V < 1 || c.d_t < mult || c.d_d < 0) return AJ_EINVAL;
@@ -83,30 +82,22 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
     if (c.feat_offset != 0 && c.feat_offset != 1) return AJ_EINVAL;
     if (c.kernel < AJ_KERNEL_AUTO || c.kernel > AJ_KERNEL_PAIR9) return AJ_EINVAL;
     if ((int64_t)c.B * (c.K + 1) > (int64_t)1 << 24) return AJ_EINVAL;
+    // vocabulary indices go through 24-bit multiplies (tile offsets, the sampling generator's first step)
+    if (c.V >= (1 << 24)) return AJ_EINVAL;
 
-    aj_handle *h = new (std::nothrow) aj_handle();
-    if (!h) return AJ_ENOMEM;
     h->cfg = c;
     h->M = c.B * (c.K + 1);
     hipError_t e = hipGetDevice(&h->device);
-    if (e != hipSuccess) {
-        delete h;
-        return hip_fail(e);
-    }
+    if (e != hipSuccess) return hip_fail(e);
     e = hipDeviceGetAttribute(&h->num_cus, hipDeviceAttributeMultiprocessorCount, h->device);
-    if (e != hipSuccess) {
-        delete h;
-        return hip_fail(e);
-    }
+    if (e != hipSuccess) return hip_fail(e);
     if (c.w_dtype != AJ_W_SAME && c.w_dtype != AJ_W_FP8_E4M3) {
-        delete h;
         return AJ_EINVAL;
     }
     if (c.w_dtype == AJ_W_FP8_E4M3) {
         // FP8 weights: the W_lm-streaming kernel only, and no top-K baseline (its pre-pass reads W_lm rows)
         if (c.dtype != AJ_BF16 || (c.flags & AJ_FLAG_TOPK) || (c.kernel != AJ_KERNEL_AUTO && c.kernel != AJ_KERNEL_STREAM) ||
             (h->M > 0 && !lm_head_stream16_fp8w_supports(h->M, c.V, c.d_t))) {
-            delete h;
             return AJ_EINVAL;
         }
         h->variant = AJ_KERNEL_STREAM;
@@ -115,11 +106,11 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
         h->nblocks = lm_head_stream16_blocks(c.V, h->num_cus);
     } else if (c.dtype == AJ_F32) {
         if (c.kernel != AJ_KERNEL_AUTO) {
-            delete h;
             return AJ_EINVAL;
         }
         h->variant = -1;
         h->nblocks = lm_head_f32_blocks(c.V);
+        if (h->nblocks > 65535) return AJ_EINVAL;   // one vocabulary block per gridDim.y entry
     } else {
         int v = c.kernel;
         if (v == AJ_KERNEL_AUTO) {
@@ -158,9 +149,9 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
         } else if (v == AJ_KERNEL_PAIR || v == AJ_KERNEL_PAIR9 ? (h->M > 0 && !lm_head_pair_supports(h->M, c.V, c.d_t))
                    : v != AJ_KERNEL_TILE && h->M > 0 && !lm_head_mfma_supports(v, h->M, c.V, c.d_t) &&
                          !(v == AJ_KERNEL_STREAM && lm_head_stream16_supports(h->M, c.V, c.d_t))) {
-            delete h;
             return AJ_EINVAL;   // a forced variant that cannot run this shape
         }
+        if (v == AJ_KERNEL_TILE && lm_head_tile_blocks(c.V) > 65535) return AJ_EINVAL;   // gridDim.y
         h->variant = v;
         h->stream16 = v == AJ_KERNEL_STREAM && lm_head_stream16_supports(h->M, c.V, c.d_t);
         h->nblocks = v == AJ_KERNEL_TILE ? lm_head_tile_blocks(c.V)
@@ -168,6 +159,21 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
                      : v == AJ_KERNEL_PAIR9 ? lm_head_pair9_blocks(c.V)
                      : h->stream16     ? lm_head_stream16_blocks(c.V, h->num_cus)
                                        : lm_head_mfma_blocks(v, c.V, c.d_t, h->num_cus);
+    }
+    return AJ_OK;
+}
+
+extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
+{
+    if (out) *out = nullptr;
+    if (!cfg || !out) return AJ_EINVAL;
+    const aj_config &c = *cfg;
+    aj_handle *h = new (std::nothrow) aj_handle();
+    if (!h) return AJ_ENOMEM;
+    const int rc = plan_handle(c, h);
+    if (rc != AJ_OK) {
+        delete h;
+        return rc;
     }
     if (h->M > 0) {
         const size_t np = (size_t)h->nblocks * h->M;
@@ -192,7 +198,7 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
         h->ev_ok = true;
         for (int i = 0; i < 64; ++i)
             for (int j = 0; j < 2; ++j) {
-                e = hipEventCreate(&h->ev[i][j]);
+                const hipError_t e = hipEventCreate(&h->ev[i][j]);
                 if (e != hipSuccess) {   // destroy what exists, then fail
                     for (int ii = 0; ii <= i; ++ii)
                         for (int jj = 0; jj < (ii == i ? j : 2); ++jj) (void)hipEventDestroy(h->ev[ii][jj]);

@@ -38,9 +38,13 @@ def _digest(a):
     return hashlib.sha256(np.ascontiguousarray(a).tobytes()).hexdigest()
 
 
-def load_golden(x):
-    """Stored oracle greedy rows for a full-size workload, or None if absent / inputs differ."""
-    path = os.path.join(GOLDEN, f"greedy_{x.w.name}_seed{x.seed}.txt")
+class GoldenMismatch(AssertionError):
+    """A stored oracle file exists but was made from other inputs than the regenerated ones."""
+
+
+def read_golden(name, seed):
+    """(digests, rows) of a stored oracle file, or None when there is no such file."""
+    path = os.path.join(GOLDEN, f"greedy_{name}_seed{seed}.txt")
     if not os.path.exists(path):
         return None
     sha, rows = {}, []
@@ -52,11 +56,25 @@ def load_golden(x):
             sha[p[1]] = p[2]
         else:
             rows.append((int(p[1]), float(p[2]), float(p[3])))
-    if len(rows) != x.w.M:
+    return sha, rows
+
+
+def load_golden(x):
+    """Stored oracle greedy rows for a full-size workload; None only when no file is stored.
+
+    A stored file whose digests or row count do not fit the regenerated inputs is an error (GoldenMismatch names
+    the tensor): silently comparing fewer rows instead would hide which check ran."""
+    got = read_golden(x.w.name, x.seed)
+    if got is None:
         return None
+    sha, rows = got
+    if len(rows) != x.w.M:
+        raise GoldenMismatch(f"golden file of {x.w.name} holds {len(rows)} rows, the workload has {x.w.M}")
     for name, arr in (("hidden_t", x.ht), ("W_lm", x.W), ("hidden_d", x.hd), ("clf_w", x.cw)):
         if sha.get(name) != _digest(arr):
-            return None
+            raise GoldenMismatch(f"golden file of {x.w.name}: regenerated {name} differs from the tensor the "
+                                 f"stored oracle rows were computed from (sha256 {sha.get(name)} stored, "
+                                 f"{_digest(arr)} regenerated)")
     t = np.array([r[0] for r in rows], np.int32)
     m1 = np.array([r[1] for r in rows], np.float64)
     m2 = np.array([r[2] for r in rows], np.float64)

@@ -88,3 +88,22 @@ def test_draft_tokens_clustered_runs():
             else:
                 j += 1
     assert 2.1 < np.mean(runs) < 2.5
+
+
+@pytest.mark.parametrize("name", ["8b_b1_k16", "70b_b8_k32"])
+def test_stored_oracle_rows_fit_the_regenerated_inputs(name):
+    """The full-size GPU parity tests trust tests/golden/greedy_*.txt only if the inputs they regenerate are the
+    bytes those rows were computed from.  The same digests, checked here without a GPU, for a 4096- and an
+    8192-wide workload (the other two stored files share these W_lm tensors)."""
+    import hashlib
+    import sys
+    import os
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    from parity import read_golden
+    w = wl.WORKLOADS[name]
+    sha, rows = read_golden(name, wl.DEFAULT_SEED)
+    assert len(rows) == w.M
+    tensors = {"hidden_t": wl.hidden_t, "W_lm": wl.w_lm, "hidden_d": wl.hidden_d, "clf_w": wl.clf_w}
+    for key, make in tensors.items():
+        got = hashlib.sha256(np.ascontiguousarray(make(w, wl.DEFAULT_SEED)).tobytes()).hexdigest()
+        assert got == sha[key], f"{name}: regenerated {key} is not the tensor the stored oracle rows were made from"

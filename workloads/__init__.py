@@ -1,6 +1,6 @@
 """Seeded synthetic speculation-window workloads.
 
-The five workloads are shaped like Llama-3-class draft/target pairs (the paper's
+The workloads are shaped like Llama-3-class draft/target pairs (the paper's
 Section 4 model pairs and window sizes); they stand in for the paper's GSM8K /
 LiveCodeBench speculation windows, which need datasets and trained weights.
 
@@ -83,6 +83,10 @@ WORKLOADS = {
                  (0.0, 0.3, 0.5, 1.0)),
         Workload("70b_b8_k32", 8, 32, 8192, 4096, 128256, "bf16", 0.7, False, -1.0, 0.5),
         Workload("70b_b128_k64", 128, 64, 8192, 4096, 128256, "bf16", 0.5, False, 0.0, 0.6),
+        # the paper's own deployment shape (Section 4.1: window 64; the serving tables: window 32): one
+        # sequence, a 70B-class target, recipe of the 70B batch-8 workload
+        Workload("70b_b1_k32", 1, 32, 8192, 4096, 128256, "bf16", 0.7, False, -1.0, 0.5),
+        Workload("70b_b1_k64", 1, 64, 8192, 4096, 128256, "bf16", 0.7, False, -1.0, 0.5),
     ]
 }
 
