@@ -60,7 +60,8 @@ typedef enum {
     AJ_EINVAL = -1,  /* null pointer, bad shape, tau outside [0,1] or NaN, misaligned pointer */
     AJ_ENOMEM = -2,  /* workspace allocation failed */
     AJ_EHIP = -3,    /* a HIP call failed; aj_last_hip_error() has the hipError_t */
-    AJ_ESTATE = -4   /* call not valid for this handle (e.g. debug data not enabled) */
+    AJ_ESTATE = -4,  /* call not valid for this handle (e.g. debug data not enabled) */
+    AJ_ELIMIT = -5   /* aj_verify_static: the shape needs more workspace than the static buffer holds */
 } aj_status;
 
 enum {
@@ -111,6 +112,26 @@ int aj_create(const aj_config *cfg, aj_handle **out);
 int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_d, const void *W_lm,
               const int32_t *draft_tok, const void *clf_w, float clf_b, float tau,
               int32_t *out_len, int32_t *out_tok, void *stream);
+
+/*
+ * aj_verify for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  No handle: the call takes the configuration itself (flags must be 0) and keeps its
+ * workspace (per-block maxima, greedy tokens) in a static device array of AJ_STATIC_SCRATCH_BYTES that every GPU
+ * the library runs on holds until the process ends.  It calls no hipMalloc / hipFree or any other allocating
+ * routine; the first call on a device looks the array's address up once.  Same kernels, same results and same
+ * errors as aj_create + aj_verify, plus
+ *   AJ_ELIMIT when B*(K+1) * (partials per row) * 8 + 2 * B*(K+1) * 4 bytes (each part rounded up to 256)
+ *             exceed AJ_STATIC_SCRATCH_BYTES: e.g. 70B-shaped, 8 windows x 33 rows needs 1.1 MB and fits,
+ *             128 windows x 65 rows needs 33 MB and does not; use a handle for those;
+ *   AJ_EINVAL when cfg->flags != 0 (debug scores, profiling and the top-K workspace live in handles).
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (different streams or
+ * threads) race; calls on one stream are ordered and safe.  Nothing in the array has to start at zero - every
+ * word a call reads it has written itself - so a call is not affected by what the previous one left.
+ */
+#define AJ_STATIC_SCRATCH_BYTES (8u << 20)
+int aj_verify_static(const aj_config *cfg, const void *hidden_t, const void *hidden_d, const void *W_lm,
+                     const int32_t *draft_tok, const void *clf_w, float clf_b, float tau,
+                     int32_t *out_len, int32_t *out_tok, void *stream);
 
 /*
  * The same steps on draft TREES (Section 3.3, "Generality": the judge applies to tree-based verification

@@ -19,7 +19,7 @@ AJ_FLAG_DEBUG, AJ_FLAG_PROFILE, AJ_FLAG_TOPK = 1, 2, 4
 AJ_W_SAME, AJ_W_FP8_E4M3 = 0, 1
 AJ_KERNEL_AUTO, AJ_KERNEL_TILE, AJ_KERNEL_STREAM, AJ_KERNEL_BIG, AJ_KERNEL_TALL, AJ_KERNEL_PAIR, AJ_KERNEL_PAIR9 = 0, 1, 2, 3, 4, 5, 6
 
-SYMBOLS = ["aj_create", "aj_verify", "aj_verify_sampled", "aj_verify_tree", "aj_verify_topk", "aj_debug_copy_rank", "aj_destroy", "aj_debug_ptrs", "aj_debug_copy", "aj_debug_logits",
+SYMBOLS = ["aj_create", "aj_verify", "aj_verify_static", "aj_verify_sampled", "aj_verify_tree", "aj_verify_topk", "aj_debug_copy_rank", "aj_destroy", "aj_debug_ptrs", "aj_debug_copy", "aj_debug_logits",
            "aj_profile_read", "aj_kernel_name", "aj_strerror", "aj_last_hip_error"]
 
 
@@ -58,6 +58,8 @@ def load_library():
     lib.aj_create.restype = ctypes.c_int
     lib.aj_verify.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, vp, vp, vp]
     lib.aj_verify.restype = ctypes.c_int
+    lib.aj_verify_static.argtypes = [ctypes.POINTER(_Config), vp, vp, vp, vp, vp, f32, f32, vp, vp, vp]
+    lib.aj_verify_static.restype = ctypes.c_int
     lib.aj_verify_sampled.argtypes = [vp, vp, vp, vp, vp, vp, f32, f32, f32, vp, vp, vp, vp]
     lib.aj_verify_sampled.restype = ctypes.c_int
     lib.aj_verify_tree.argtypes = [vp, vp, vp, vp, vp, vp, vp, f32, f32, vp, vp, vp, vp]
@@ -132,6 +134,17 @@ def aj_verify(h, hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, out_len
                                   _stream(stream))
     if rc != 0:
         raise AjError(rc, "aj_verify")
+
+
+def aj_verify_static(B, K, d_t, d_d, V, dtype, feat_offset, kernel, hidden_t, hidden_d, W_lm, draft_tok, clf_w,
+                     clf_b, tau, out_len, out_tok, stream=None, flags=0, w_dtype=AJ_W_SAME):
+    """aj_verify without a handle or any allocation (workspace in the library's static device array)."""
+    cfg = _Config(B, K, d_t, d_d, V, dtype, feat_offset, flags, kernel, w_dtype)
+    rc = load_library().aj_verify_static(ctypes.byref(cfg), _ptr(hidden_t), _ptr(hidden_d), _ptr(W_lm),
+                                         _ptr(draft_tok), _ptr(clf_w), float(clf_b), float(tau), _ptr(out_len),
+                                         _ptr(out_tok), _stream(stream))
+    if rc != 0:
+        raise AjError(rc, "aj_verify_static")
 
 
 def aj_verify_sampled(h, hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, inv_temperature, row_key,

@@ -1,5 +1,6 @@
 // C ABI of libaj (declared in include/aj.h): argument checks, workspace, kernel dispatch.
 #include <math.h>
+#include <mutex>
 #include <new>
 
 #include "../../include/aj.h"
@@ -48,6 +49,7 @@ extern "C" const char *aj_strerror(int status)
         case AJ_ENOMEM: return "device workspace allocation failed";
         case AJ_EHIP: return "a HIP call failed (see aj_last_hip_error)";
         case AJ_ESTATE: return "call not valid for this handle";
+        case AJ_ELIMIT: return "the shape needs more workspace than the static buffer of aj_verify_static holds";
         default: return "unknown status";
     }
 }
@@ -306,6 +308,59 @@ extern "C" int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_
                          int32_t *out_len, int32_t *out_tok, void *stream)
 {
     return verify_common(h, hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, nullptr, 1.f, nullptr, nullptr,
+                         out_len, out_tok, stream);
+}
+
+// ---- aj_verify without any allocation: the workspace is a static device array -----------------------------
+// Every GPU the library runs on holds its own copy of `scratch` at its own address until the process ends.  In
+// host code the array's NAME is only a stand-in: the device address comes from hipGetSymbolAddress, once per
+// device with that device current, and that pointer is what kernels get.
+static __device__ __align__(256) unsigned char scratch[AJ_STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[MAX_DEVICES];   // device address of `scratch` per device, nullptr until first use
+
+static int scratch_of_current_device(int device, unsigned char **out)
+{
+    if (device < 0 || device >= MAX_DEVICES) return AJ_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (!p) return hip_fail(hipErrorInvalidSymbol);
+        g_scratch_ptr[device] = p;
+    }
+    *out = (unsigned char *)g_scratch_ptr[device];
+    return AJ_OK;
+}
+
+static size_t round256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+extern "C" int aj_verify_static(const aj_config *cfg, const void *hidden_t, const void *hidden_d, const void *W_lm,
+                                const int32_t *draft_tok, const void *clf_w, float clf_b, float tau,
+                                int32_t *out_len, int32_t *out_tok, void *stream)
+{
+    if (!cfg) return AJ_EINVAL;
+    if (cfg->flags != 0) return AJ_EINVAL;        // debug scores, profiling events and top-K counts need a handle
+    aj_handle h = {};
+    const int rc = plan_handle(*cfg, &h);          // validates, chooses the kernel; allocates nothing
+    if (rc != AJ_OK) return rc;
+    if (h.M == 0) return AJ_OK;
+    // workspace of this shape: [M][nblocks] partials, then t_star[M] and maxlogit[M], each 256-byte aligned
+    const size_t part_bytes = round256((size_t)h.M * h.nblocks * sizeof(Best));
+    const size_t row_bytes = round256((size_t)h.M * sizeof(int32_t));
+    if (part_bytes + 2 * row_bytes > AJ_STATIC_SCRATCH_BYTES) return AJ_ELIMIT;
+    unsigned char *base = nullptr;
+    const int rs = scratch_of_current_device(h.device, &base);
+    if (rs != AJ_OK) return rs;
+    // every word the tail kernel reads is written by the LM-head kernel of the same call (one partial per row and
+    // block, empty blocks included), so nothing has to start at zero and the last call's contents do not matter
+    h.part = (Best *)base;
+    h.t_star = (int32_t *)(base + part_bytes);
+    h.maxlogit = (float *)(base + part_bytes + row_bytes);
+    return verify_common(&h, hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, nullptr, 1.f, nullptr, nullptr,
                          out_len, out_tok, stream);
 }
 
