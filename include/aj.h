@@ -74,7 +74,7 @@ enum { AJ_W_SAME = 0, AJ_W_FP8_E4M3 = 1 };
 
 /* LM-head kernel choice; AJ_KERNEL_AUTO picks by shape. The others force one for tests/benchmarks. */
 enum { AJ_KERNEL_AUTO = 0, AJ_KERNEL_TILE = 1, AJ_KERNEL_STREAM = 2, AJ_KERNEL_BIG = 3, AJ_KERNEL_TALL = 4,
-       AJ_KERNEL_PAIR = 5, AJ_KERNEL_PAIR9 = 6 };
+       AJ_KERNEL_PAIR = 5, AJ_KERNEL_PAIR9 = 6, AJ_KERNEL_RESIDENT = 7 };
 
 typedef struct {
     int32_t B;           /* windows per call, >= 0 (0: the call does nothing) */
@@ -120,7 +120,7 @@ int aj_verify(aj_handle *h, const void *hidden_t, const void *hidden_d, const vo
  * the library runs on holds until the process ends.  It calls no hipMalloc / hipFree or any other allocating
  * routine; the first call on a device looks the array's address up once.  Same kernels, same results and same
  * errors as aj_create + aj_verify, plus
- *   AJ_ELIMIT when B*(K+1) * (partials per row) * 8 + 2 * B*(K+1) * 4 bytes (each part rounded up to 256)
+ *   AJ_ELIMIT when B*(K+1) * (partials per row) * 8 + 3 * B*(K+1) * 4 bytes (each part rounded up to 256)
  *             exceed AJ_STATIC_SCRATCH_BYTES: e.g. 70B-shaped, 8 windows x 33 rows needs 1.1 MB and fits,
  *             128 windows x 65 rows needs 33 MB and does not; use a handle for those;
  *   AJ_EINVAL when cfg->flags != 0 (debug scores, profiling and the top-K workspace live in handles).

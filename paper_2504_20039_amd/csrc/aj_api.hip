@@ -21,6 +21,7 @@ struct aj_handle {
     int32_t *t_star;
     float *maxlogit;
     float *score;  // [2][B][K] or nullptr
+    uint8_t *rej;  // [B][K] rejected-slot flags (tail kernels' split form)
     // top-K baseline workspace (AJ_FLAG_TOPK)
     int32_t *cnt;      // [M][nblocks]
     float *thr;        // [M]
@@ -62,6 +63,7 @@ static void free_all(aj_handle *h)
     if (h->t_star) (void)hipFree(h->t_star);
     if (h->maxlogit) (void)hipFree(h->maxlogit);
     if (h->score) (void)hipFree(h->score);
+    if (h->rej) (void)hipFree(h->rej);
     if (h->cnt) (void)hipFree(h->cnt);
     if (h->thr) (void)hipFree(h->thr);
     if (h->thr_tok) (void)hipFree(h->thr_tok);
@@ -82,7 +84,7 @@ static int plan_handle(const aj_config &c, aj_handle *h)
     if (c.B < 0 || c.K < 1 || c.K > 1023 || c.V < 1 || c.d_t < mult || c.d_d < 0) return AJ_EINVAL;
     if (c.d_t % mult || c.d_d % mult) return AJ_EINVAL;
     if (c.feat_offset != 0 && c.feat_offset != 1) return AJ_EINVAL;
-    if (c.kernel < AJ_KERNEL_AUTO || c.kernel > AJ_KERNEL_PAIR9) return AJ_EINVAL;
+    if (c.kernel < AJ_KERNEL_AUTO || c.kernel > AJ_KERNEL_RESIDENT) return AJ_EINVAL;
     if ((int64_t)c.B * (c.K + 1) > (int64_t)1 << 24) return AJ_EINVAL;
     // vocabulary indices go through 24-bit multiplies (tile offsets, the sampling generator's first step)
     if (c.V >= (1 << 24)) return AJ_EINVAL;
@@ -97,15 +99,23 @@ static int plan_handle(const aj_config &c, aj_handle *h)
         return AJ_EINVAL;
     }
     if (c.w_dtype == AJ_W_FP8_E4M3) {
-        // FP8 weights: the W_lm-streaming kernel only, and no top-K baseline (its pre-pass reads W_lm rows)
-        if (c.dtype != AJ_BF16 || (c.flags & AJ_FLAG_TOPK) || (c.kernel != AJ_KERNEL_AUTO && c.kernel != AJ_KERNEL_STREAM) ||
-            (h->M > 0 && !lm_head_stream16_fp8w_supports(h->M, c.V, c.d_t))) {
-            return AJ_EINVAL;
-        }
-        h->variant = AJ_KERNEL_STREAM;
-        h->stream16 = true;
+        // FP8 weights: the two W_lm-streaming kernels only (up to 128 verify rows), and no top-K baseline (its
+        // pre-pass reads W_lm rows)
+        if (c.dtype != AJ_BF16 || (c.flags & AJ_FLAG_TOPK)) return AJ_EINVAL;
+        const bool s16 = (c.kernel == AJ_KERNEL_AUTO || c.kernel == AJ_KERNEL_STREAM) &&
+                         lm_head_stream16_fp8w_supports(h->M, c.V, c.d_t);
+        const bool res = (c.kernel == AJ_KERNEL_AUTO || c.kernel == AJ_KERNEL_RESIDENT) &&
+                         lm_head_resident_supports(h->M, c.V, c.d_t, true);
+        if (h->M > 0 && !s16 && !res) return AJ_EINVAL;
         h->fp8w = true;
-        h->nblocks = lm_head_stream16_blocks(c.V, h->num_cus);
+        if (s16 || h->M == 0) {
+            h->variant = AJ_KERNEL_STREAM;
+            h->stream16 = true;
+            h->nblocks = lm_head_stream16_blocks(c.V, h->num_cus);
+        } else {
+            h->variant = AJ_KERNEL_RESIDENT;
+            h->nblocks = lm_head_resident_blocks(c.V, h->num_cus);
+        }
     } else if (c.dtype == AJ_F32) {
         if (c.kernel != AJ_KERNEL_AUTO) {
             return AJ_EINVAL;
@@ -127,8 +137,11 @@ static int plan_handle(const aj_config &c, aj_handle *h)
             // padded tile still wins over the general 128 x 128 kernel: the step is bound by streaming W_lm,
             // which these pipelines do at 4.2-4.9 TB/s against 2.2-3.8 (34..255 rows, same device).  The general
             // kernel serves what is left: hidden sizes that are not a multiple of 32.
-            if (lm_head_stream16_supports(h->M, c.V, c.d_t) ||
-                lm_head_mfma_supports(AJ_KERNEL_STREAM, h->M, c.V, c.d_t)) {
+            if (lm_head_stream16_supports(h->M, c.V, c.d_t)) {
+                v = AJ_KERNEL_STREAM;
+            } else if (lm_head_resident_supports(h->M, c.V, c.d_t, false)) {
+                v = AJ_KERNEL_RESIDENT;     // up to 128 rows at any hidden size that is a multiple of 256
+            } else if (lm_head_mfma_supports(AJ_KERNEL_STREAM, h->M, c.V, c.d_t)) {
                 v = AJ_KERNEL_STREAM;
             } else {
                 const bool pair = lm_head_pair_supports(h->M, c.V, c.d_t);
@@ -148,6 +161,8 @@ static int plan_handle(const aj_config &c, aj_handle *h)
                         best = k.cost;
                     }
             }
+        } else if (v == AJ_KERNEL_RESIDENT) {
+            if (h->M > 0 && !lm_head_resident_supports(h->M, c.V, c.d_t, false)) return AJ_EINVAL;
         } else if (v == AJ_KERNEL_PAIR || v == AJ_KERNEL_PAIR9 ? (h->M > 0 && !lm_head_pair_supports(h->M, c.V, c.d_t))
                    : v != AJ_KERNEL_TILE && h->M > 0 && !lm_head_mfma_supports(v, h->M, c.V, c.d_t) &&
                          !(v == AJ_KERNEL_STREAM && lm_head_stream16_supports(h->M, c.V, c.d_t))) {
@@ -159,6 +174,7 @@ static int plan_handle(const aj_config &c, aj_handle *h)
         h->nblocks = v == AJ_KERNEL_TILE ? lm_head_tile_blocks(c.V)
                      : v == AJ_KERNEL_PAIR ? lm_head_pair_blocks(c.V)
                      : v == AJ_KERNEL_PAIR9 ? lm_head_pair9_blocks(c.V)
+                     : v == AJ_KERNEL_RESIDENT ? lm_head_resident_blocks(c.V, h->num_cus)
                      : h->stream16     ? lm_head_stream16_blocks(c.V, h->num_cus)
                                        : lm_head_mfma_blocks(v, c.V, c.d_t, h->num_cus);
     }
@@ -181,7 +197,8 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
         const size_t np = (size_t)h->nblocks * h->M;
         bool ok = hipMalloc(&h->part, np * sizeof(Best)) == hipSuccess &&
                   hipMalloc(&h->t_star, (size_t)h->M * sizeof(int32_t)) == hipSuccess &&
-                  hipMalloc(&h->maxlogit, (size_t)h->M * sizeof(float)) == hipSuccess;
+                  hipMalloc(&h->maxlogit, (size_t)h->M * sizeof(float)) == hipSuccess &&
+                  hipMalloc(&h->rej, (size_t)h->M) == hipSuccess;
         if (ok && (c.flags & AJ_FLAG_DEBUG))
             ok = hipMalloc(&h->score, (size_t)2 * c.B * c.K * sizeof(float)) == hipSuccess;
         if (ok && (c.flags & AJ_FLAG_TOPK))
@@ -242,6 +259,8 @@ static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void 
     a.inv_temp = inv_temp;
     if (h->variant < 0) return lm_head_f32(a, s);
     if (h->variant == AJ_KERNEL_TILE) return lm_head_tile_bf16(a, s);
+    if (h->variant == AJ_KERNEL_RESIDENT)
+        return h->fp8w ? lm_head_resident_fp8w(a, h->num_cus, s) : lm_head_resident_bf16(a, h->num_cus, s);
     if (h->fp8w) return lm_head_stream16_fp8w(a, h->num_cus, s);
     if (h->stream16) return lm_head_stream16_bf16(a, h->num_cus, s);
     if (h->variant == AJ_KERNEL_PAIR) return lm_head_pair_bf16(a, h->num_cus, s);
@@ -295,6 +314,7 @@ static int verify_common(aj_handle *h, const void *hidden_t, const void *hidden_
     t.t_star = h->t_star;
     t.maxlogit = h->maxlogit;
     t.score = h->score;
+    t.rej = h->rej;
     t.out_len = out_len;
     t.out_tok = out_tok;
     t.parent = parent;
@@ -348,10 +368,11 @@ extern "C" int aj_verify_static(const aj_config *cfg, const void *hidden_t, cons
     const int rc = plan_handle(*cfg, &h);          // validates, chooses the kernel; allocates nothing
     if (rc != AJ_OK) return rc;
     if (h.M == 0) return AJ_OK;
-    // workspace of this shape: [M][nblocks] partials, then t_star[M] and maxlogit[M], each 256-byte aligned
+    // workspace of this shape: [M][nblocks] partials, then t_star[M], maxlogit[M] and the rejected-slot flags
+    // (M bytes), each 256-byte aligned
     const size_t part_bytes = round256((size_t)h.M * h.nblocks * sizeof(Best));
     const size_t row_bytes = round256((size_t)h.M * sizeof(int32_t));
-    if (part_bytes + 2 * row_bytes > AJ_STATIC_SCRATCH_BYTES) return AJ_ELIMIT;
+    if (part_bytes + 3 * row_bytes > AJ_STATIC_SCRATCH_BYTES) return AJ_ELIMIT;
     unsigned char *base = nullptr;
     const int rs = scratch_of_current_device(h.device, &base);
     if (rs != AJ_OK) return rs;
@@ -360,6 +381,7 @@ extern "C" int aj_verify_static(const aj_config *cfg, const void *hidden_t, cons
     h.part = (Best *)base;
     h.t_star = (int32_t *)(base + part_bytes);
     h.maxlogit = (float *)(base + part_bytes + row_bytes);
+    h.rej = base + part_bytes + 2 * row_bytes;
     return verify_common(&h, hidden_t, hidden_d, W_lm, draft_tok, clf_w, clf_b, tau, nullptr, 1.f, nullptr, nullptr,
                          out_len, out_tok, stream);
 }
@@ -504,6 +526,7 @@ extern "C" const char *aj_kernel_name(const aj_handle *h)
         case AJ_KERNEL_TALL: return "lm_head_tall_bf16";
         case AJ_KERNEL_PAIR: return "lm_head_pair_bf16";
         case AJ_KERNEL_PAIR9: return "lm_head_pair9_bf16";
+        case AJ_KERNEL_RESIDENT: return h->fp8w ? "lm_head_resident_fp8w" : "lm_head_resident_bf16";
         default: return "unknown";
     }
 }

@@ -77,6 +77,17 @@ __device__ __forceinline__ float gumbel_noise(uint32_t klo, uint32_t khi, uint32
     return -0.69314718f * __builtin_amdgcn_logf(e);
 }
 
+// 8 OCP FP8 E4M3 values -> 8 bf16, exactly (E4M3 has 4 significant bits and a narrower exponent range)
+__device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint2 raw)
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw.x, true);
+    const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw.y, false), e = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw.y, true);
+    auto pack = [](float lo, float hi) { return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xffff0000u); };
+    u32x4 w = {pack(a[0], a[1]), pack(b[0], b[1]), pack(c[0], c[1]), pack(e[0], e[1])};
+    return __builtin_bit_cast(bf16x8, w);
+}
+
 // Number of vocabulary blocks (partials per row) each variant produces for V.
 int lm_head_tile_blocks(int V);
 int lm_head_f32_blocks(int V);
@@ -96,6 +107,13 @@ hipError_t lm_head_stream16_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s
 // the same kernel with W_lm stored as OCP FP8 E4M3 (hidden_t stays bf16): M <= 32, d_t = 4096
 bool lm_head_stream16_fp8w_supports(int M, int V, int d);
 hipError_t lm_head_stream16_fp8w(const LmHeadArgs &a, int num_cus, hipStream_t s);
+
+// W_lm-streaming kernel with the logits resident in registers for the whole kernel (M <= 128, d_t % 256 == 0);
+// W_lm in bf16 or as OCP FP8 E4M3 bytes (hidden_t stays bf16)
+bool lm_head_resident_supports(int M, int V, int d, bool fp8w);
+int lm_head_resident_blocks(int V, int num_cus);
+hipError_t lm_head_resident_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s);
+hipError_t lm_head_resident_fp8w(const LmHeadArgs &a, int num_cus, hipStream_t s);
 
 // 256 x 256 tiles with paired 64-byte half loads (whole 128-byte lines per request pair); d_t % 256 == 0
 bool lm_head_pair_supports(int M, int V, int d);
@@ -119,6 +137,7 @@ struct TailArgs {
     int32_t *t_star;        // [M] out
     float *maxlogit;        // [M] out
     float *score;           // [B][K] out or nullptr
+    uint8_t *rej;           // [B][K] workspace of the split form: 1 = slot rejected (nullptr: one-launch form only)
     int32_t *out_len, *out_tok;
     // draft trees (nullptr for chains): parent[B][K] in [-1, j), and the accepted node per window
     const int32_t *parent;

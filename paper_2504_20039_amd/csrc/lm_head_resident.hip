@@ -1,0 +1,333 @@
+// LM head (step 1) + greedy maximum (first half of step 2) for the W_lm-streaming regime at up to 128 verify
+// rows and any hidden size that is a multiple of 256: the logits stay in registers for the WHOLE kernel.
+//
+// hidden_t of 33..128 rows at d_t = 8192 fits neither the registers nor the LDS of a compute unit, so a kernel
+// that walks vocabulary tiles has to stream the hidden_t tile again for every W_lm tile (as much L2 -> CU
+// traffic as W_lm itself at 128 x 128).  What does fit is the OUTPUT: a compute unit's share of the vocabulary
+// (V / 256 = 501 rows) x 128 verify rows x 4 bytes = 256 KB of its 512 KB of registers.  So the loops are turned
+// inside out:
+//
+//   * every wave owns 64 vocabulary rows (4 blocks of 16; 8 waves = 512 rows per workgroup, one workgroup per
+//     compute unit) and keeps their logits against all verify rows in accumulators - 4 x MB blocks of
+//     v_mfma_f32_16x16x32_bf16, MB = ceil(M / 16) <= 8 - from the first k element to the last; the greedy
+//     maximum is taken once, at the end.  A vocabulary larger than grid x 512 rows takes several such passes;
+//   * k advances in slabs of 256 elements.  The hidden_t slab (M rows x 512 B) is staged in LDS, double
+//     buffered, by asynchronous direct-to-LDS loads shared among the 8 waves: ONE workgroup barrier per slab,
+//     and every compute unit reads hidden_t exactly once per pass;
+//   * W_lm goes global -> registers in MFMA fragment layout, never through LDS: lane (row l%16, k group l/16)
+//     loads the 16 bytes the matrix instruction wants from it, so one load instruction covers 16 rows x 64
+//     contiguous bytes and eight consecutive loads of a block pair walk 512 contiguous bytes of each of 32 rows
+//     (few rows with long runs is what the HBM likes).  The loads are ordinary non-temporal loads in a ring
+//     of 16 registers sets per wave: a fragment is used, then its registers are refilled with the fragment 16
+//     loads ahead, so 16 KB per wave (128 KB per compute unit) are always in flight and the compiler's own
+//     s_waitcnt accounting waits for exactly the load that is needed;
+//   * FP8W: W_lm stored as OCP FP8 E4M3.  A 16-byte load then holds 16 k elements = the lane's share of TWO k
+//     steps; the bytes are widened exactly to bf16 in registers, so the MFMAs see the values of the bf16 path.
+#include "../../include/aj.h"
+#include "aj_internal.h"
+#include "lds_pipeline.h"
+#include <stdlib.h>
+
+namespace aj {
+
+namespace {
+
+constexpr int RS_WAVES = 8;
+constexpr int RS_NBW = 4;                       // 16-row vocabulary blocks per wave and pass
+constexpr int RS_KS = 256;                      // k elements per slab
+constexpr int RS_HROW = RS_KS * 2;              // bytes of a hidden_t row per slab
+
+template <int MB, bool FP8W, bool DUMP, bool TOPK, bool SAMPLE>
+__global__ __launch_bounds__(RS_WAVES * 64) void k_lm_head_resident(LmHeadArgs a, int passes, int rot_step)
+{
+    constexpr int HSLAB = MB * 16 * RS_HROW;                 // bytes of a hidden_t slab in LDS
+    constexpr int WSEG = FP8W ? RS_KS : RS_KS * 2;           // bytes of a W_lm row per slab
+    constexpr int USES = WSEG / 64 * RS_NBW;                 // fragment loads per wave and slab: 32 (bf16), 16 (FP8)
+    // hidden_t fragment sets: two (the next pair's k step is read during this one's MFMAs) while registers allow
+    constexpr int HFB = MB * (FP8W ? 2 : 1) <= 6 ? 2 : 1;
+    // W_lm fragment loads in flight per wave (1 KB each): 16 while the accumulators leave room, 8 from 6 row blocks on
+    constexpr int RS_RING = MB <= 5 ? 16 : 8;
+    __shared__ __attribute__((aligned(1024))) char lds[2 * HSLAB];
+    __shared__ Best fin[RS_WAVES][MB * 16];
+    __shared__ int32_t finc[TOPK ? RS_WAVES : 1][MB * 16];
+
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l16 = lane & 15, q4 = lane >> 4;
+    const char *W = (const char *)a.W, *H = (const char *)a.H;
+    const uint32_t wrow = (uint32_t)a.d * (FP8W ? 1u : 2u);     // bytes of a W_lm row
+    const uint32_t hrow = (uint32_t)a.d * 2u;                   // bytes of a hidden_t row
+    const int NS = a.d / RS_KS;                                 // slabs per pass
+    const int nwaves = gridDim.x * RS_WAVES, gw = blockIdx.x * RS_WAVES + wave;
+    const int rot = (int)((blockIdx.x * (unsigned)rot_step) % (unsigned)NS);   // this workgroup's first slab
+    const int total = passes * NS;
+
+    // ---- hidden_t slab loader: load i of wave w fills LDS rows 2*(8i + w) and the next; lane (row half lane/32,
+    // chunk slot lane%32) fetches global chunk slot ^ (row % 16), so that fragment reads are conflict free
+    const uint32_t lds_base = lds_offset_of(lds);
+    const int tr0 = 2 * wave + (lane >> 5);             // the lane's LDS row in load 0; load i: + 16 * i
+    const uint32_t hchunk = (uint32_t)(((lane & 31) ^ (tr0 & 15)) * 16);
+    auto load_h = [&](int slab, int buf) {
+        const char *hb = H + (size_t)slab * RS_HROW;
+#pragma unroll
+        for (int i = 0; i < MB; ++i)    // rows beyond M repeat the last one (their logits are never looked at)
+            lds_dma_16(hb, __umul24(min(tr0 + 16 * i, a.M - 1), hrow) + hchunk,
+                       lds_base + buf * HSLAB + (i * RS_WAVES + wave) * 1024);
+    };
+    // slab of iteration `it` (k rotation per workgroup)
+    auto slab_of = [&](int it) {
+        int s = it % NS + rot;
+        return s >= NS ? s - NS : s;
+    };
+    // lane offsets of the wave's 4 vocabulary blocks in the pass of iteration `it`, clamped into W_lm
+    auto w_offsets = [&](int it, uint32_t(&wo)[RS_NBW]) {
+        const int v0 = ((it / NS) * nwaves + gw) * (RS_NBW * 16);
+#pragma unroll
+        for (int b = 0; b < RS_NBW; ++b) wo[b] = __umul24(min(v0 + b * 16 + l16, a.V - 1), wrow) + (uint32_t)q4 * 16u;
+    };
+    // W_lm fragment loads are buffer loads: lane offset + uniform slab offset + immediate, with the non-temporal
+    // bit (W_lm is read exactly once) as an operand of the instruction, which no compiler pass can drop
+    const __amdgpu_buffer_rsrc_t wres =
+        __builtin_amdgcn_make_buffer_rsrc((void *)a.W, 0, (int)((uint32_t)a.V * wrow), 0x00020000);
+    // use u of a slab: block 2*(u / (USES/2)) + u % 2, 64-byte piece (u % (USES/2)) / 2 of the row's slab segment
+    auto w_load = [&](const uint32_t(&wo)[RS_NBW], int slab_off, int u) {
+        constexpr int HALF = USES / 2;
+        const int blk = 2 * (u / HALF) + (u & 1), piece = (u % HALF) >> 1;
+        return __builtin_amdgcn_raw_buffer_load_b128(wres, (int)wo[blk] + piece * 64, slab_off, 2 /* nt */);
+    };
+
+    f32x4 acc[RS_NBW][MB];
+#pragma unroll
+    for (int y = 0; y < MB; ++y) {
+#pragma unroll
+        for (int b = 0; b < RS_NBW; ++b) acc[b][y] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // the wave's running (maximum, lowest index) and top-K count per verify row live in its own row of
+        // `fin` between passes, not in registers; only this wave touches them until the final merge
+        if (q4 == 0) {
+            fin[wave][y * 16 + l16] = Best{-INFINITY, 0x7fffffff};
+            if (TOPK) finc[wave][y * 16 + l16] = 0;
+        }
+    }
+
+    // a wave whose first row lies beyond the vocabulary in pass 0 never computes: it only helps to stage hidden_t
+    const bool active = gw * (RS_NBW * 16) < a.V;
+
+    uint32_t wcur[RS_NBW], wnxt[RS_NBW];
+    int scur = slab_of(0) * WSEG, snxt = 0;          // byte offset of the slab in a W_lm row
+    u32x4 ring[RS_RING];
+    load_h(slab_of(0), 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    w_offsets(0, wcur);
+    if (active) {
+#pragma unroll
+        for (int u = 0; u < RS_RING; ++u) ring[u] = w_load(wcur, scur, u);
+    }
+
+    for (int it = 0; it < total; ++it) {
+        const int buf = it & 1;
+        // slab `it` has landed: its loads are older than the USES fragment loads this wave has issued since
+        if (it > 0) {
+            if (active) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(USES) : "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+        // every wave's part of the slab is in LDS, and every wave has finished reading the other buffer
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        const bool more = it + 1 < total;
+        if (more) load_h(slab_of(it + 1), buf ^ 1);
+        // after the last slab the ring refills with data nobody uses
+        w_offsets(more ? it + 1 : it, wnxt);
+        snxt = slab_of(more ? it + 1 : it) * WSEG;
+
+        if (active) {
+            const char *hs = lds + buf * HSLAB + l16 * RS_HROW;
+            constexpr int HALF = USES / 2, NK = FP8W ? 2 : 1;      // NK: k steps per fragment load
+            // hidden_t fragments of the k step(s) of uses u0, u0 + 1 (the two blocks of a pair share them)
+            auto read_h = [&](int u0, bf16x8(&hf)[NK][MB]) {
+                const int piece = (u0 % HALF) >> 1;
+#pragma unroll
+                for (int y = 0; y < MB; ++y)
+#pragma unroll
+                    for (int k = 0; k < NK; ++k) {
+                        // FP8W: the lane's 16 bytes are k elements 64*piece + 16*q4 .. + 15, two k steps of 8 each
+                        const int chunk = FP8W ? 8 * piece + 2 * q4 + k : 4 * piece + q4;
+                        hf[k][y] = *(const bf16x8 *)(hs + y * 16 * RS_HROW + ((chunk ^ l16) * 16));
+                    }
+            };
+            // The order below is the order of execution (sched_barrier): left to itself the compiler sinks every
+            // refill load to just before its use, which empties the ring.
+            bf16x8 hf[HFB][NK][MB];
+            read_h(0, hf[0]);
+#pragma unroll
+            for (int u0 = 0; u0 < USES; u0 += 2) {
+                const int cur = HFB == 2 ? (u0 >> 1) & 1 : 0;
+                if (HFB == 2 && u0 + 2 < USES) read_h(u0 + 2, hf[cur ^ 1]);
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    const int u = u0 + b, blk = 2 * (u / HALF) + b;
+                    const u32x4 raw = ring[u % RS_RING];
+                    if (FP8W) {
+                        const bf16x8 f0 = fp8x8_to_bf16x8(uint2{raw[0], raw[1]}), f1 = fp8x8_to_bf16x8(uint2{raw[2], raw[3]});
+#pragma unroll
+                        for (int y = 0; y < MB; ++y) {
+                            acc[blk][y] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0, hf[cur][0][y], acc[blk][y], 0, 0, 0);
+                            acc[blk][y] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1, hf[cur][NK - 1][y], acc[blk][y], 0, 0, 0);
+                        }
+                    } else {
+                        const bf16x8 f0 = __builtin_bit_cast(bf16x8, raw);
+#pragma unroll
+                        for (int y = 0; y < MB; ++y)
+                            acc[blk][y] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0, hf[cur][0][y], acc[blk][y], 0, 0, 0);
+                    }
+                    // refill: the fragment RS_RING loads ahead (same slab, or the next iteration's)
+                    ring[u % RS_RING] = u + RS_RING < USES ? w_load(wcur, scur, u + RS_RING) : w_load(wnxt, snxt, u + RS_RING - USES);
+                }
+                if (HFB == 1 && u0 + 2 < USES) read_h(u0 + 2, hf[0]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < RS_NBW; ++b) wcur[b] = wnxt[b];
+        scur = snxt;
+
+        if ((it + 1) % NS == 0 && active) {
+            // ---- end of a pass: lane (l16, q4) holds verify row 16y + l16 against vocabulary rows
+            // v0 + 16b + 4*q4 + r of its wave, ascending in (b, r): strict > keeps the lowest
+            const int v0 = ((it / NS) * nwaves + gw) * (RS_NBW * 16);
+#pragma unroll
+            for (int y = 0; y < MB; ++y) {
+                const int row = y * 16 + l16, rowc = min(row, a.M - 1);
+                float th = INFINITY;
+                int32_t tk = -1;
+                if (TOPK) {
+                    th = a.thr[rowc];
+                    tk = a.thr_tok[rowc];
+                }
+                uint32_t klo = 0, khi = 0;
+                if (SAMPLE) {
+                    const uint64_t key = a.key[rowc];
+                    klo = (uint32_t)key;
+                    khi = (uint32_t)(key >> 32);
+                }
+                float bv = -INFINITY;
+                int32_t bi = 0x7fffffff, cn = 0;
+#pragma unroll
+                for (int b = 0; b < RS_NBW; ++b) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int v = v0 + b * 16 + q4 * 4 + r;
+                        float val = acc[b][y][r];
+                        if (v < a.V) {
+                            if (DUMP && row < a.M) a.dump[(size_t)row * a.V + v] = val;
+                            if (SAMPLE) val = fmaf(val, a.inv_temp, gumbel_noise(klo, khi, (uint32_t)v));
+                            if (val > bv) {
+                                bv = val;
+                                bi = v;
+                            }
+                            if (TOPK) cn += ranks_before(val, v, th, tk);
+                        }
+                    }
+                    acc[b][y] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+                // the 4 vocabulary sub-rows of a lane group, then what earlier passes left
+#pragma unroll
+                for (int off = 16; off <= 32; off <<= 1) {
+                    const float ov = __shfl_xor(bv, off);
+                    const int32_t oi = __shfl_xor(bi, off);
+                    if (better(ov, oi, bv, bi)) {
+                        bv = ov;
+                        bi = oi;
+                    }
+                    if (TOPK) cn += __shfl_xor(cn, off);
+                }
+                if (q4 == 0) {
+                    const Best o = fin[wave][row];
+                    if (better(bv, bi, o.v, o.i)) fin[wave][row] = Best{bv, bi};
+                    if (TOPK) finc[wave][row] += cn;
+                }
+            }
+            // the slab wait above counts this wave's loads: let the logit dump's stores retire here
+            if (DUMP) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+    }
+
+    // ---- merge the 8 waves
+    __syncthreads();
+    if ((int)threadIdx.x < MB * 16 && (int)threadIdx.x < a.M) {
+        const int row = threadIdx.x;
+        Best best = fin[0][row];
+        int32_t cn = TOPK ? finc[0][row] : 0;
+#pragma unroll
+        for (int w = 1; w < RS_WAVES; ++w) {
+            const Best o = fin[w][row];
+            if (better(o.v, o.i, best.v, best.i)) best = o;
+            if (TOPK) cn += finc[w][row];
+        }
+        a.part[(size_t)row * a.nblocks + blockIdx.x] = best;
+        if (TOPK) a.cnt[(size_t)row * a.nblocks + blockIdx.x] = cn;
+    }
+}
+
+int resident_grid(int V, int num_cus)
+{
+    const int nb = (V + 15) / 16;                                        // 16-row vocabulary blocks
+    return persistent_grid(num_cus, (nb + RS_WAVES * RS_NBW - 1) / (RS_WAVES * RS_NBW));
+}
+
+template <int MB, bool FP8W>
+hipError_t launch_resident(const LmHeadArgs &a, int num_cus, hipStream_t s)
+{
+    const int grid = resident_grid(a.V, num_cus);
+    const int nb = (a.V + 15) / 16, per_pass = grid * RS_WAVES * RS_NBW;
+    const int passes = (nb + per_pass - 1) / per_pass;
+    // workgroups start at different slabs (5 apart): at any moment the chip reads many k offsets of W_lm, not the
+    // same column of every row
+    static const int rot_env = getenv("AJ_ROT") ? atoi(getenv("AJ_ROT")) : 5;   // TEMP: measurement knob
+    const int rot_step = rot_env;
+    const dim3 g(grid), b(RS_WAVES * 64);
+    if (a.dump) hipLaunchKernelGGL((k_lm_head_resident<MB, FP8W, true, false, false>), g, b, 0, s, a, passes, rot_step);
+    else if (a.thr) hipLaunchKernelGGL((k_lm_head_resident<MB, FP8W, false, true, false>), g, b, 0, s, a, passes, rot_step);
+    else if (a.key) hipLaunchKernelGGL((k_lm_head_resident<MB, FP8W, false, false, true>), g, b, 0, s, a, passes, rot_step);
+    else hipLaunchKernelGGL((k_lm_head_resident<MB, FP8W, false, false, false>), g, b, 0, s, a, passes, rot_step);
+    return hipGetLastError();
+}
+
+template <bool FP8W>
+hipError_t dispatch_resident(const LmHeadArgs &a, int num_cus, hipStream_t s)
+{
+    switch ((a.M + 15) / 16) {
+        case 1: return launch_resident<1, FP8W>(a, num_cus, s);
+        case 2: return launch_resident<2, FP8W>(a, num_cus, s);
+        case 3: return launch_resident<3, FP8W>(a, num_cus, s);
+        case 4: return launch_resident<4, FP8W>(a, num_cus, s);
+        case 5: return launch_resident<5, FP8W>(a, num_cus, s);
+        case 6: return launch_resident<6, FP8W>(a, num_cus, s);
+        case 7: return launch_resident<7, FP8W>(a, num_cus, s);
+        case 8: return launch_resident<8, FP8W>(a, num_cus, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+bool lm_head_resident_supports(int M, int V, int d, bool fp8w)
+{
+    if (M <= 0 || M > 128 || V <= 0 || d <= 0 || d % RS_KS != 0) return false;
+    // 32-bit lane offsets, 24-bit multiplies
+    if ((uint64_t)V * d * (fp8w ? 1 : 2) >= (1ull << 32) || (uint64_t)M * d * 2 >= (1ull << 32)) return false;
+    return V < (1 << 24) && d * 2 < (1 << 24);
+}
+
+int lm_head_resident_blocks(int V, int num_cus) { return resident_grid(V, num_cus); }
+
+hipError_t lm_head_resident_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s)
+{
+    if (a.M <= 0) return hipSuccess;
+    return dispatch_resident<false>(a, num_cus, s);
+}
+
+hipError_t lm_head_resident_fp8w(const LmHeadArgs &a, int num_cus, hipStream_t s)
+{
+    if (a.M <= 0) return hipSuccess;
+    return dispatch_resident<true>(a, num_cus, s);
+}
+
+}  // namespace aj

@@ -37,17 +37,6 @@ constexpr int S16_SEG = 512;                    // bytes of each row per stage (
 constexpr int S16_STAGE = S16_ROWS * S16_SEG;   // 8 KB = eight 1 KB loads
 constexpr int S16_LOADS = S16_STAGE / 1024;
 
-// 8 OCP FP8 E4M3 values -> 8 bf16, exactly (E4M3 has 4 significant bits and a narrower exponent range)
-__device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(uint2 raw)
-{
-    typedef float f32x2 __attribute__((ext_vector_type(2)));
-    const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw.x, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw.x, true);
-    const f32x2 c = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw.y, false), e = __builtin_amdgcn_cvt_pk_f32_fp8((int)raw.y, true);
-    auto pack = [](float lo, float hi) { return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xffff0000u); };
-    u32x4 w = {pack(a[0], a[1]), pack(b[0], b[1]), pack(c[0], c[1]), pack(e[0], e[1])};
-    return __builtin_bit_cast(bf16x8, w);
-}
-
 template <int NST, bool DUMP, bool TOPK, bool SAMPLE, bool FP8W>   // NST stages per tile and wave: d_t = NST * 2048 (4096 with FP8W)
 __global__ __launch_bounds__(S16_WAVES * 64) void k_lm_head_stream16(LmHeadArgs a, int ntiles)
 {

@@ -27,7 +27,7 @@ def fp8_case(w, seed, tau=None, repeat=1, sampled=None):
         def scores_row(r):
             return oracle.logits_row(x.ht[r], x.W) * sampled[0] + np.array([oracle.gumbel(int(keys[r]), v) for v in range(w.V)])
     rep = compare(x, draft, tau, greedy, gpu, scores_row=scores_row)
-    assert gpu["kernel"] == "lm_head_stream16_fp8w"
+    assert gpu["kernel"] == ("lm_head_stream16_fp8w" if w.M <= 32 and w.d_t == 4096 else "lm_head_resident_fp8w")
     return rep, x, w8, gpu
 
 
@@ -36,6 +36,10 @@ def fp8_case(w, seed, tau=None, repeat=1, sampled=None):
     dict(B=2, K=15, V=9000),           # all 32 rows
     dict(B=1, K=4, V=40),              # fewer tiles than workgroups
     dict(B=3, K=7, V=70001),           # more tiles than workgroups: several per workgroup
+    dict(B=1, K=32, V=5003, d_t=8192),     # 33 rows at the 70B hidden size: the accumulator-resident kernel
+    dict(B=1, K=64, V=140000, d_t=1024),   # 65 rows; more vocabulary than one pass holds
+    dict(B=4, K=31, V=3000, d_t=512),      # 128 rows: all eight row blocks
+    dict(B=2, K=15, V=1000, d_t=2048),     # 32 rows at a hidden size the 16-row-tile kernel does not take in FP8
 ])
 def test_fp8_weights(shape):
     w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="fp8", p_match=0.6, **shape)
@@ -67,7 +71,7 @@ def test_fp8_sampling_and_full_size():
 def test_fp8_refusals():
     import paper_2504_20039_amd as aj
     ok = dict(B=1, K=16, d_t=4096, d_d=64, V=1000)
-    for bad in (dict(d_t=2048), dict(B=3), dict(dtype=aj.AJ_F32), dict(flags=aj.AJ_FLAG_TOPK), dict(kernel=aj.AJ_KERNEL_PAIR),
+    for bad in (dict(d_t=4096 + 64), dict(B=8), dict(dtype=aj.AJ_F32), dict(flags=aj.AJ_FLAG_TOPK), dict(kernel=aj.AJ_KERNEL_PAIR),
                 dict(w_dtype=7)):
         a = dict(ok, dtype=aj.AJ_BF16, flags=0, kernel=0, w_dtype=aj.AJ_W_FP8_E4M3)
         a.update(bad)
