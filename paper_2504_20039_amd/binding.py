@@ -12,7 +12,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libaj.so")
+# AJ_LIBRARY (environment) names another build of the library, e.g. one with profiling or ablation switches
+_LIB_PATH = os.environ.get("AJ_LIBRARY") or os.path.join(_HERE, "libaj.so")
 
 AJ_F32, AJ_BF16 = 0, 1
 AJ_FLAG_DEBUG, AJ_FLAG_PROFILE, AJ_FLAG_TOPK = 1, 2, 4

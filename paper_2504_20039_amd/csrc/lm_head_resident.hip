@@ -14,19 +14,19 @@
 //   * k advances in slabs of 256 elements.  The hidden_t slab (M rows x 512 B) is staged in LDS, double
 //     buffered, by asynchronous direct-to-LDS loads shared among the 8 waves: ONE workgroup barrier per slab,
 //     and every compute unit reads hidden_t exactly once per pass;
-//   * W_lm goes global -> registers in MFMA fragment layout, never through LDS: lane (row l%16, k group l/16)
-//     loads the 16 bytes the matrix instruction wants from it, so one load instruction covers 16 rows x 64
-//     contiguous bytes and eight consecutive loads of a block pair walk 512 contiguous bytes of each of 32 rows
-//     (few rows with long runs is what the HBM likes).  The loads are ordinary non-temporal loads in a ring
-//     of 16 registers sets per wave: a fragment is used, then its registers are refilled with the fragment 16
-//     loads ahead, so 16 KB per wave (128 KB per compute unit) are always in flight and the compiler's own
-//     s_waitcnt accounting waits for exactly the load that is needed;
+//   * W_lm goes global -> registers, never through LDS, by non-temporal buffer loads that the compiler's own
+//     s_waitcnt accounting tracks.  A wave visits its 4 blocks one after the other within a slab; the 8 loads of
+//     a visit (16 rows x 512 contiguous bytes) go out in one burst, one visit before their use, so 8 KB per wave
+//     (64 KB per compute unit) are always in flight.  Every load instruction asks for WHOLE 128-byte lines (8 rows
+//     x 128 B): with the non-temporal bit, half lines per instruction (the MFMA's own 16 rows x 64 B) stream at
+//     5.9 TB/s in a load-only kernel, whole lines at 6.6.  The halves reach the MFMA layout by one DPP rotation
+//     per register (see w_load / half_of).  Measured on the 70B shapes: 16 x 64 B loads refilled one by one 5.5
+//     TB/s, the same in bursts per block 5.9, whole lines 6.7; a deeper ring changed nothing;
 //   * FP8W: W_lm stored as OCP FP8 E4M3.  A 16-byte load then holds 16 k elements = the lane's share of TWO k
 //     steps; the bytes are widened exactly to bf16 in registers, so the MFMAs see the values of the bf16 path.
 #include "../../include/aj.h"
 #include "aj_internal.h"
 #include "lds_pipeline.h"
-#include <stdlib.h>
 
 namespace aj {
 
@@ -45,8 +45,11 @@ __global__ __launch_bounds__(RS_WAVES * 64) void k_lm_head_resident(LmHeadArgs a
     constexpr int USES = WSEG / 64 * RS_NBW;                 // fragment loads per wave and slab: 32 (bf16), 16 (FP8)
     // hidden_t fragment sets: two (the next pair's k step is read during this one's MFMAs) while registers allow
     constexpr int HFB = MB * (FP8W ? 2 : 1) <= 6 ? 2 : 1;
-    // W_lm fragment loads in flight per wave (1 KB each): 16 while the accumulators leave room, 8 from 6 row blocks on
-    constexpr int RS_RING = MB <= 5 ? 16 : 8;
+    // A wave visits its 4 vocabulary blocks one after the other within a slab.  The fragments of a visit (UPV
+    // loads of 1 KB: 16 rows x 64 * UPV contiguous bytes) are requested in one burst, AHEAD visits before their use,
+    // into one of NG register groups.
+    constexpr int UPV = USES / RS_NBW;                       // 8 (bf16), 4 (FP8)
+    constexpr int NG = FP8W && MB <= 5 ? 4 : 2, AHEAD = NG - 1;
     __shared__ __attribute__((aligned(1024))) char lds[2 * HSLAB];
     __shared__ Best fin[RS_WAVES][MB * 16];
     __shared__ int32_t finc[TOPK ? RS_WAVES : 1][MB * 16];
@@ -78,21 +81,36 @@ __global__ __launch_bounds__(RS_WAVES * 64) void k_lm_head_resident(LmHeadArgs a
         int s = it % NS + rot;
         return s >= NS ? s - NS : s;
     };
-    // lane offsets of the wave's 4 vocabulary blocks in the pass of iteration `it`, clamped into W_lm
-    auto w_offsets = [&](int it, uint32_t(&wo)[RS_NBW]) {
-        const int v0 = ((it / NS) * nwaves + gw) * (RS_NBW * 16);
-#pragma unroll
-        for (int b = 0; b < RS_NBW; ++b) wo[b] = __umul24(min(v0 + b * 16 + l16, a.V - 1), wrow) + (uint32_t)q4 * 16u;
-    };
-    // W_lm fragment loads are buffer loads: lane offset + uniform slab offset + immediate, with the non-temporal
-    // bit (W_lm is read exactly once) as an operand of the instruction, which no compiler pass can drop
+    // W_lm fragment loads are buffer loads (lane offset + uniform offset + immediate) with the non-temporal bit -
+    // W_lm is read exactly once - as an operand of the instruction, which no compiler pass can drop.  With that
+    // bit a load instruction has to ask for WHOLE 128-byte lines: 16 rows x 64 B per instruction (the MFMA's own
+    // layout) streams at 5.9 TB/s in a load-only kernel, 8 rows x 128 B at 6.6.  So load 2*pr + h of a block
+    // visit covers rows 8h .. 8h+7 of the block x line pr of the slab segment: lane (l16, q4) asks for row
+    // l16 % 8 and the 16 bytes at (q4 + 4 * (l16 / 8)) * 16 of the line.  The two loads of a line pair then hold,
+    // for 64-byte half c of the line, rows 0..7 in lanes l16 / 8 == c of the first and rows 8..15 in the same
+    // lanes of the second: one rotation by 8 lanes within each group of 16 (a DPP move) per register gives the
+    // MFMA layout (lane l16 <-> row l16) of both halves.
     const __amdgpu_buffer_rsrc_t wres =
         __builtin_amdgcn_make_buffer_rsrc((void *)a.W, 0, (int)((uint32_t)a.V * wrow), 0x00020000);
-    // use u of a slab: block 2*(u / (USES/2)) + u % 2, 64-byte piece (u % (USES/2)) / 2 of the row's slab segment
-    auto w_load = [&](const uint32_t(&wo)[RS_NBW], int slab_off, int u) {
-        constexpr int HALF = USES / 2;
-        const int blk = 2 * (u / HALF) + (u & 1), piece = (u % HALF) >> 1;
-        return __builtin_amdgcn_raw_buffer_load_b128(wres, (int)wo[blk] + piece * 64, slab_off, 2 /* nt */);
+    // first vocabulary row of this wave in the pass of iteration `it`
+    auto w_first = [&](int it) { return ((it / NS) * nwaves + gw) * (RS_NBW * 16); };
+    const int r8 = l16 & 7;
+    const uint32_t cbyte = (uint32_t)(q4 + 4 * (l16 >> 3)) * 16u;
+    // load j = 2*pr + h of the visit to block blk of the wave whose first row is v0; slab_off: byte offset of the
+    // slab in a row (uniform).  Rows are clamped into the vocabulary (their logits are never looked at).
+    auto w_load = [&](int v0, int slab_off, int blk, int j) {
+        const int row = min(v0 + blk * 16 + (j & 1) * 8 + r8, a.V - 1);
+        return __builtin_amdgcn_raw_buffer_load_b128(wres, (int)(__umul24(row, wrow) + cbyte) + (j >> 1) * 128,
+                                                     slab_off, 2 /* nt */);
+    };
+    // 64-byte half c of a line pair (x: rows 0..7, y: rows 8..15) in MFMA layout
+    auto half_of = [&](const u32x4 &x, const u32x4 &y, int c) {
+        u32x4 r;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            r[k] = c == 0 ? (uint32_t)__builtin_amdgcn_update_dpp((int)x[k], (int)y[k], 0x128 /* row_ror:8 */, 0xF, 0xC, false)
+                          : (uint32_t)__builtin_amdgcn_update_dpp((int)y[k], (int)x[k], 0x128, 0xF, 0x3, false);
+        return r;
     };
 
     f32x4 acc[RS_NBW][MB];
@@ -111,15 +129,17 @@ __global__ __launch_bounds__(RS_WAVES * 64) void k_lm_head_resident(LmHeadArgs a
     // a wave whose first row lies beyond the vocabulary in pass 0 never computes: it only helps to stage hidden_t
     const bool active = gw * (RS_NBW * 16) < a.V;
 
-    uint32_t wcur[RS_NBW], wnxt[RS_NBW];
+    int wcur, wnxt;
     int scur = slab_of(0) * WSEG, snxt = 0;          // byte offset of the slab in a W_lm row
-    u32x4 ring[RS_RING];
+    u32x4 ring[NG][UPV];
     load_h(slab_of(0), 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    w_offsets(0, wcur);
+    wcur = w_first(0);
     if (active) {
 #pragma unroll
-        for (int u = 0; u < RS_RING; ++u) ring[u] = w_load(wcur, scur, u);
+        for (int v = 0; v < AHEAD; ++v)
+#pragma unroll
+            for (int p = 0; p < UPV; ++p) ring[v][p] = w_load(wcur, scur, v, p);
     }
 
     for (int it = 0; it < total; ++it) {
@@ -134,58 +154,64 @@ __global__ __launch_bounds__(RS_WAVES * 64) void k_lm_head_resident(LmHeadArgs a
         const bool more = it + 1 < total;
         if (more) load_h(slab_of(it + 1), buf ^ 1);
         // after the last slab the ring refills with data nobody uses
-        w_offsets(more ? it + 1 : it, wnxt);
+        wnxt = w_first(more ? it + 1 : it);
         snxt = slab_of(more ? it + 1 : it) * WSEG;
 
         if (active) {
             const char *hs = lds + buf * HSLAB + l16 * RS_HROW;
-            constexpr int HALF = USES / 2, NK = FP8W ? 2 : 1;      // NK: k steps per fragment load
-            // hidden_t fragments of the k step(s) of uses u0, u0 + 1 (the two blocks of a pair share them)
-            auto read_h = [&](int u0, bf16x8(&hf)[NK][MB]) {
-                const int piece = (u0 % HALF) >> 1;
+            constexpr int NK = FP8W ? 2 : 1;      // k steps per fragment load
+            // hidden_t fragments of the k step(s) of piece p of the slab (the same for every vocabulary block)
+            auto read_h = [&](int p, bf16x8(&hf)[NK][MB]) {
 #pragma unroll
                 for (int y = 0; y < MB; ++y)
 #pragma unroll
                     for (int k = 0; k < NK; ++k) {
-                        // FP8W: the lane's 16 bytes are k elements 64*piece + 16*q4 .. + 15, two k steps of 8 each
-                        const int chunk = FP8W ? 8 * piece + 2 * q4 + k : 4 * piece + q4;
+                        // FP8W: the lane's 16 bytes are k elements 64*p + 16*q4 .. + 15, two k steps of 8 each
+                        const int chunk = FP8W ? 8 * p + 2 * q4 + k : 4 * p + q4;
                         hf[k][y] = *(const bf16x8 *)(hs + y * 16 * RS_HROW + ((chunk ^ l16) * 16));
                     }
             };
             // The order below is the order of execution (sched_barrier): left to itself the compiler sinks every
-            // refill load to just before its use, which empties the ring.
+            // load to just before its use, which empties the ring.
             bf16x8 hf[HFB][NK][MB];
             read_h(0, hf[0]);
 #pragma unroll
-            for (int u0 = 0; u0 < USES; u0 += 2) {
-                const int cur = HFB == 2 ? (u0 >> 1) & 1 : 0;
-                if (HFB == 2 && u0 + 2 < USES) read_h(u0 + 2, hf[cur ^ 1]);
+            for (int v = 0; v < RS_NBW; ++v) {
+                // a burst of UPV loads: the 16 rows of the block visited AHEAD visits from now, 64 * UPV contiguous
+                // bytes of each, into the registers of the visit that has just ended
+                {
+                    constexpr int dummy = 0;
+                    (void)dummy;
+                    const int vv = v + AHEAD;
 #pragma unroll
-                for (int b = 0; b < 2; ++b) {
-                    const int u = u0 + b, blk = 2 * (u / HALF) + b;
-                    const u32x4 raw = ring[u % RS_RING];
+                    for (int p = 0; p < UPV; ++p)
+                        ring[vv % NG][p] = vv < RS_NBW ? w_load(wcur, scur, vv, p) : w_load(wnxt, snxt, vv - RS_NBW, p);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int p = 0; p < UPV; ++p) {
+                    const int u = v * UPV + p, cur = HFB == 2 ? u & 1 : 0;
+                    if (HFB == 2 && u + 1 < USES) read_h((p + 1) % UPV, hf[cur ^ 1]);
+                    const u32x4 raw = half_of(ring[v % NG][p & ~1], ring[v % NG][p | 1], p & 1);
                     if (FP8W) {
                         const bf16x8 f0 = fp8x8_to_bf16x8(uint2{raw[0], raw[1]}), f1 = fp8x8_to_bf16x8(uint2{raw[2], raw[3]});
 #pragma unroll
                         for (int y = 0; y < MB; ++y) {
-                            acc[blk][y] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0, hf[cur][0][y], acc[blk][y], 0, 0, 0);
-                            acc[blk][y] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1, hf[cur][NK - 1][y], acc[blk][y], 0, 0, 0);
+                            acc[v][y] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0, hf[cur][0][y], acc[v][y], 0, 0, 0);
+                            acc[v][y] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1, hf[cur][NK - 1][y], acc[v][y], 0, 0, 0);
                         }
                     } else {
                         const bf16x8 f0 = __builtin_bit_cast(bf16x8, raw);
 #pragma unroll
                         for (int y = 0; y < MB; ++y)
-                            acc[blk][y] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0, hf[cur][0][y], acc[blk][y], 0, 0, 0);
+                            acc[v][y] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0, hf[cur][0][y], acc[v][y], 0, 0, 0);
                     }
-                    // refill: the fragment RS_RING loads ahead (same slab, or the next iteration's)
-                    ring[u % RS_RING] = u + RS_RING < USES ? w_load(wcur, scur, u + RS_RING) : w_load(wnxt, snxt, u + RS_RING - USES);
+                    if (HFB == 1 && u + 1 < USES) read_h((p + 1) % UPV, hf[0]);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                if (HFB == 1 && u0 + 2 < USES) read_h(u0 + 2, hf[0]);
-                __builtin_amdgcn_sched_barrier(0);
             }
         }
-#pragma unroll
-        for (int b = 0; b < RS_NBW; ++b) wcur[b] = wnxt[b];
+        wcur = wnxt;
         scur = snxt;
 
         if ((it + 1) % NS == 0 && active) {
@@ -280,8 +306,7 @@ hipError_t launch_resident(const LmHeadArgs &a, int num_cus, hipStream_t s)
     const int passes = (nb + per_pass - 1) / per_pass;
     // workgroups start at different slabs (5 apart): at any moment the chip reads many k offsets of W_lm, not the
     // same column of every row
-    static const int rot_env = getenv("AJ_ROT") ? atoi(getenv("AJ_ROT")) : 5;   // TEMP: measurement knob
-    const int rot_step = rot_env;
+    const int rot_step = 5;
     const dim3 g(grid), b(RS_WAVES * 64);
     if (a.dump) hipLaunchKernelGGL((k_lm_head_resident<MB, FP8W, true, false, false>), g, b, 0, s, a, passes, rot_step);
     else if (a.thr) hipLaunchKernelGGL((k_lm_head_resident<MB, FP8W, false, true, false>), g, b, 0, s, a, passes, rot_step);

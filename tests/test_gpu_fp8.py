@@ -58,6 +58,30 @@ def test_fp8_weights(shape):
     assert np.abs(logits.cpu().numpy() - ref).max() <= 1e-4 * np.abs(ref).max()
 
 
+@pytest.mark.parametrize("B,K,d_t", [(2, 15, 4096), (4, 31, 256)])      # the 16-row-tile kernel; the accumulator-resident one
+def test_every_fp8_code_is_widened_exactly(B, K, d_t):
+    """One-hot hidden rows turn the logit dump into a read-out of the weights as the kernel sees them: every finite
+    E4M3 code (subnormals, both zeros, +-448) must come out as the format defines it, bit for bit."""
+    import torch
+    import paper_2504_20039_amd as aj
+    M, V = B * (K + 1), 512
+    v, k = np.meshgrid(np.arange(V), np.arange(d_t), indexing="ij")
+    w8 = ((v + 3 * k) % 256).astype(np.uint8)
+    w8[(w8 & 0x7F) == 0x7F] = 0x38                    # the two NaN codes -> 1.0
+    ht = np.zeros((M, d_t), np.uint16)
+    ht[np.arange(M), (np.arange(M) * 7) % d_t] = 0x3F80      # bf16 1.0 at column 7r of row r
+    h = aj.aj_create(B, K, d_t, 64, V, aj.AJ_BF16, 1, 0, 0, aj.AJ_W_FP8_E4M3)
+    logits = torch.empty((M, V), dtype=torch.float32, device="cuda")
+    aj.aj_debug_logits(h, aj.device_tensor(ht), aj.device_tensor(w8), logits)
+    torch.cuda.synchronize()
+    aj.aj_destroy(h)
+    want = wl.widen(wl.fp8_e4m3_to_bf16_bits(w8))[:, (np.arange(M) * 7) % d_t].T      # [M][V]
+    got = logits.cpu().numpy()
+    assert set(np.unique(w8)) >= set(range(0, 0x7F)) | set(range(0x80, 0xFF))
+    assert np.array_equal(got.view(np.uint32) & 0x7FFFFFFF, want.astype(np.float32).view(np.uint32) & 0x7FFFFFFF)
+    assert np.array_equal(got, want)
+
+
 def test_fp8_sampling_and_full_size():
     w = wl.WORKLOADS["8b_b1_k16"]
     rep, x, w8, gpu = fp8_case(w, wl.DEFAULT_SEED, repeat=2)
