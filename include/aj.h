@@ -74,7 +74,7 @@ enum { AJ_W_SAME = 0, AJ_W_FP8_E4M3 = 1 };
 
 /* LM-head kernel choice; AJ_KERNEL_AUTO picks by shape. The others force one for tests/benchmarks. */
 enum { AJ_KERNEL_AUTO = 0, AJ_KERNEL_TILE = 1, AJ_KERNEL_STREAM = 2, AJ_KERNEL_BIG = 3, AJ_KERNEL_TALL = 4,
-       AJ_KERNEL_PAIR = 5, AJ_KERNEL_PAIR9 = 6, AJ_KERNEL_RESIDENT = 7 };
+       AJ_KERNEL_PAIR = 5, AJ_KERNEL_PAIR9 = 6, AJ_KERNEL_RESIDENT = 7, AJ_KERNEL_WIDE = 8 };
 
 typedef struct {
     int32_t B;           /* windows per call, >= 0 (0: the call does nothing) */

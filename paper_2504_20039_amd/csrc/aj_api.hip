@@ -84,7 +84,7 @@ static int plan_handle(const aj_config &c, aj_handle *h)
     if (c.B < 0 || c.K < 1 || c.K > 1023 || c.V < 1 || c.d_t < mult || c.d_d < 0) return AJ_EINVAL;
     if (c.d_t % mult || c.d_d % mult) return AJ_EINVAL;
     if (c.feat_offset != 0 && c.feat_offset != 1) return AJ_EINVAL;
-    if (c.kernel < AJ_KERNEL_AUTO || c.kernel > AJ_KERNEL_RESIDENT) return AJ_EINVAL;
+    if (c.kernel < AJ_KERNEL_AUTO || c.kernel > AJ_KERNEL_WIDE) return AJ_EINVAL;
     if ((int64_t)c.B * (c.K + 1) > (int64_t)1 << 24) return AJ_EINVAL;
     // vocabulary indices go through 24-bit multiplies (tile offsets, the sampling generator's first step)
     if (c.V >= (1 << 24)) return AJ_EINVAL;
@@ -141,6 +141,11 @@ static int plan_handle(const aj_config &c, aj_handle *h)
                 v = AJ_KERNEL_STREAM;
             } else if (lm_head_resident_supports(h->M, c.V, c.d_t, false)) {
                 v = AJ_KERNEL_RESIDENT;     // up to 128 rows at any hidden size that is a multiple of 256
+            } else if (h->M <= 240 && lm_head_wide_supports(h->M, c.V, c.d_t)) {
+                // 129..240 rows: W_lm straight into registers, 16-row blocks (0.39 ms against 0.46 of a padded 256-row
+                // tile at 144 rows of the 70B shape, 0.48 against 0.51 at 224; from 256 rows on the LDS-fed tiles are
+                // as fast or faster)
+                v = AJ_KERNEL_WIDE;
             } else if (lm_head_mfma_supports(AJ_KERNEL_STREAM, h->M, c.V, c.d_t)) {
                 v = AJ_KERNEL_STREAM;
             } else {
@@ -163,6 +168,8 @@ static int plan_handle(const aj_config &c, aj_handle *h)
             }
         } else if (v == AJ_KERNEL_RESIDENT) {
             if (h->M > 0 && !lm_head_resident_supports(h->M, c.V, c.d_t, false)) return AJ_EINVAL;
+        } else if (v == AJ_KERNEL_WIDE) {
+            if (h->M > 0 && !lm_head_wide_supports(h->M, c.V, c.d_t)) return AJ_EINVAL;
         } else if (v == AJ_KERNEL_PAIR || v == AJ_KERNEL_PAIR9 ? (h->M > 0 && !lm_head_pair_supports(h->M, c.V, c.d_t))
                    : v != AJ_KERNEL_TILE && h->M > 0 && !lm_head_mfma_supports(v, h->M, c.V, c.d_t) &&
                          !(v == AJ_KERNEL_STREAM && lm_head_stream16_supports(h->M, c.V, c.d_t))) {
@@ -175,6 +182,7 @@ static int plan_handle(const aj_config &c, aj_handle *h)
                      : v == AJ_KERNEL_PAIR ? lm_head_pair_blocks(c.V)
                      : v == AJ_KERNEL_PAIR9 ? lm_head_pair9_blocks(c.V)
                      : v == AJ_KERNEL_RESIDENT ? lm_head_resident_blocks(c.V, h->num_cus)
+                     : v == AJ_KERNEL_WIDE ? lm_head_wide_blocks(c.V)
                      : h->stream16     ? lm_head_stream16_blocks(c.V, h->num_cus)
                                        : lm_head_mfma_blocks(v, c.V, c.d_t, h->num_cus);
     }
@@ -261,6 +269,7 @@ static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void 
     if (h->variant == AJ_KERNEL_TILE) return lm_head_tile_bf16(a, s);
     if (h->variant == AJ_KERNEL_RESIDENT)
         return h->fp8w ? lm_head_resident_fp8w(a, h->num_cus, s) : lm_head_resident_bf16(a, h->num_cus, s);
+    if (h->variant == AJ_KERNEL_WIDE) return lm_head_wide_bf16(a, h->num_cus, s);
     if (h->fp8w) return lm_head_stream16_fp8w(a, h->num_cus, s);
     if (h->stream16) return lm_head_stream16_bf16(a, h->num_cus, s);
     if (h->variant == AJ_KERNEL_PAIR) return lm_head_pair_bf16(a, h->num_cus, s);
@@ -526,6 +535,7 @@ extern "C" const char *aj_kernel_name(const aj_handle *h)
         case AJ_KERNEL_TALL: return "lm_head_tall_bf16";
         case AJ_KERNEL_PAIR: return "lm_head_pair_bf16";
         case AJ_KERNEL_PAIR9: return "lm_head_pair9_bf16";
+        case AJ_KERNEL_WIDE: return "lm_head_wide_bf16";
         case AJ_KERNEL_RESIDENT: return h->fp8w ? "lm_head_resident_fp8w" : "lm_head_resident_bf16";
         default: return "unknown";
     }

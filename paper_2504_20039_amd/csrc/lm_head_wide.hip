@@ -1,0 +1,350 @@
+// LM head (step 1) + per-vocabulary-block greedy maximum (first half of step 2) for 129..272 verify rows in ONE
+// row tile (e.g. 8 windows x 33 rows = 264): 256 vocabulary rows x 16*MB verify rows per workgroup, MB <= 17 blocks
+// of v_mfma_f32_16x16x32_bf16, so that 264 rows pad to 272 (3 %) and W_lm is streamed from HBM exactly once.
+//
+// 4 waves side by side along the vocabulary (one per SIMD, 512 registers each): a wave owns 64 vocabulary rows
+// (4 blocks of 16) against all verify rows = 4 x MB accumulator blocks of 4 registers (272 at MB = 17).
+//   * W_lm rows are private to a wave, so they never touch LDS: non-temporal buffer loads of whole 128-byte lines
+//     (8 rows x 128 B per instruction) straight into registers, brought to the MFMA layout by one DPP rotation per
+//     register, in place - the load path of lm_head_resident.hip.  A ring of 4 groups of 8 loads (64 rows x one line); a group
+//     is refilled, in one burst, right after its second half has been used: 24 KB per wave in flight, three lines
+//     (3.3 us of MFMA work) ahead.  The loads are hand-written with the kernel's own s_waitcnt accounting.
+//   * hidden_t is shared by the 4 waves: slabs of 64 k elements (16*MB rows x one 128-byte line) staged in LDS, four
+//     buffers (three slabs ahead), by asynchronous direct-to-LDS loads; one workgroup barrier per slab.  A slab is 2 pieces of 32 k; a
+//     piece is 4 x MB MFMAs ordered row block by row block.  The hidden_t fragments are a rolling window of 8: the
+//     fragment used 8 row blocks from now (in this piece or the next) is read from LDS right after the 4 MFMAs that
+//     used the slot's previous content, so the LDS latency hides behind two row blocks' MFMAs and the window costs 32
+//     registers instead of 4 * MB.  The wait + barrier for the next slab sits before the LAST piece of a slab, during
+//     which the first fragments of the new buffer are read.
+//   * 272 accumulator registers do not fit the 256 AGPRs, and left to choose the compiler moves accumulators between
+//     the two register files inside the hot loop.  So every MFMA is a hand-written statement that names the file:
+//     row blocks 0..15 in AGPRs, row block 16 (MB = 17 only) in VGPRs.
+#include "../../include/aj.h"
+#include "aj_internal.h"
+#include "lds_pipeline.h"
+
+namespace aj {
+
+namespace {
+
+constexpr int WD_WAVES = 4;
+constexpr int WD_N = 256;                       // vocabulary rows per tile
+constexpr int WD_KS = 64;                       // k elements per hidden_t slab: one 128-byte line of a row
+constexpr int WD_HROW = WD_KS * 2;              // bytes of a hidden_t row per slab
+constexpr int WD_MAXB = 17;
+
+template <int MB, bool DUMP, bool TOPK, bool SAMPLE>
+__global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, int ntiles)
+{
+    constexpr int HSLAB = MB * 16 * WD_HROW;                    // bytes of a hidden_t slab in LDS
+    constexpr int MBA = MB > 16 ? 16 : MB;                      // row blocks accumulated through the builtin
+    constexpr int NHB = 4;                                      // hidden_t slab buffers
+    __shared__ __attribute__((aligned(1024))) char lds[NHB * HSLAB];
+    __shared__ Best red[WD_WAVES][MB * 16];
+    __shared__ int32_t redc[TOPK ? WD_WAVES : 1][MB * 16];
+
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l16 = lane & 15, q4 = lane >> 4;
+    const char *H = (const char *)a.H;
+    const uint32_t wrow = (uint32_t)a.d * 2u;
+    const int NS = a.d / WD_KS;                                 // slabs (= lines) per tile: a multiple of 4 (host: d % 256 == 0)
+
+    // ---- hidden_t slab loader: a load covers 8 LDS rows x 128 B (1 KB); load i of wave w covers row group 4i + w
+    // (beyond the slab: its last group once more - same data to the same place); lane (row lane/8, chunk slot lane%8)
+    // fetches global chunk slot ^ ((row / 2) % 8), so that the fragment reads are conflict free.  The group index
+    // depends on an opaque scalar, so that each lane offset is computed here (a few VALU operations) instead of living in a
+    // register, and in scratch memory, across the kernel.
+    constexpr int HG = 2 * MB, HL = (HG + WD_WAVES - 1) / WD_WAVES;     // row groups per slab, loads per wave
+    const uint32_t lds_base = lds_offset_of(lds);
+    auto load_h = [&](int slab, int bufoff) {
+        const char *hb = H + (size_t)slab * WD_HROW;
+        int z = 0;
+        asm volatile("" : "+s"(z));                      // an opaque zero
+#pragma unroll
+        for (int i = 0; i < HL; ++i) {
+            const int gg = min(i * WD_WAVES + wave + z, HG - 1);
+            const int hr = 8 * gg + (lane >> 3);         // rows beyond M repeat the last one (their logits are never looked at)
+            lds_dma_16(hb, __umul24(min(hr, a.M - 1), wrow) + (uint32_t)(((lane & 7) ^ ((hr >> 1) & 7)) * 16),
+                       lds_base + bufoff + gg * 1024);
+        }
+    };
+
+    // ---- W_lm loads (see lm_head_resident.hip): load 2*blk + h of a line covers rows 8h .. 8h+7 of block blk
+    // The loads are hand-written, with the kernel's own s_waitcnt accounting (W_WAIT, H_WAIT below): the compiler
+    // does not count the direct-to-LDS loads, so its own waits for buffer loads issued between them come out stricter
+    // than needed and let only one line of W_lm be in flight.
+    const uint64_t wbase = (uint64_t)a.W;
+    const u32x4 wres = {(uint32_t)wbase, (uint32_t)(wbase >> 32), (uint32_t)a.V * wrow, 0x00020000u};   // raw buffer
+    const int r8 = l16 & 7;
+    const uint32_t cbyte = (uint32_t)(q4 + 4 * (l16 >> 3)) * 16u;
+    auto w_load = [&](u32x4 &dst, int v0, int line, int j) {      // line: index of the 128-byte line in the row
+        int r0 = v0 + (j >> 1) * 16 + (j & 1) * 8;      // opaque scalar: see load_h
+        asm volatile("" : "+s"(r0));
+#ifdef WD_ABLATE_W_FROM_L2
+        const int row = min(r0 + r8, a.V - 1) & 255;     // every workgroup reads the same 256 rows: W_lm from L2
+#else
+        const int row = min(r0 + r8, a.V - 1);
+#endif
+        asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen nt"
+                     : "=v"(dst)
+                     : "v"(__umul24(row, wrow) + cbyte), "s"(wres), "s"(line * 128)
+                     : "memory");
+    };
+    // The two loads of a block's line (x: rows 0..7, y: rows 8..15; lanes l16 < 8 hold the first 64 bytes, the others
+    // the second) become, in place, the block's two k steps in MFMA layout (lane l16 <-> row l16): x keeps its lower
+    // lanes and takes y's lower lanes into its upper ones, y keeps its upper lanes and takes x's upper lanes.
+    auto to_mfma_layout = [&](u32x4 &x, u32x4 &y) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int xk = (int)x[k], yk = (int)y[k];
+            x[k] = (uint32_t)__builtin_amdgcn_update_dpp(xk, yk, 0x128 /* row_ror:8 */, 0xF, 0xC, false);
+            y[k] = (uint32_t)__builtin_amdgcn_update_dpp(yk, xk, 0x128, 0xF, 0x3, false);
+        }
+    };
+
+    f32x4 acc[4][MBA], accv[4];       // accv: row block 16, in VGPRs
+    u32x4 ring[4][8];                 // 4 lines x (4 blocks x 2 halves of the block's rows)
+    constexpr int HW = MB >= 15 ? 4 : 8;   // hidden_t fragment window (registers are scarce at 15+ row blocks)
+    static_assert(MB >= HW, "the window reaches into the next piece only");
+    bf16x8 hf[HW];
+    // fragment of row block y, piece p (0, 1) of a slab: lds + buffer offset + hs[p] + y * 16 rows; the row-block part
+    // travels in the instruction's offset field
+    const int hsw = (l16 >> 1) & 7;
+    const int hs[2] = {l16 * WD_HROW + ((q4 ^ hsw) * 16), l16 * WD_HROW + (((4 + q4) ^ hsw) * 16)};
+    auto read_h = [&](const char *base, int y) { return *(const bf16x8 *)(base + y * 16 * WD_HROW); };
+
+    // one piece (p = 0, 1) of a slab: 4 x MB MFMAs with half p of ring group g.  n0 = index of the piece's first row
+    // block in the fragment sequence (mod HW); after row block y the window slot is refilled with the fragment HW
+    // positions on: this piece's (buffer cb), or the next piece's (piece np of buffer nb)
+    auto piece = [&](int g, int p, int n0, int cb, int nb, int np) {
+        // the buffer offsets stay opaque run-time values: folded into constants (they cycle with the 4 slabs of a trip)
+        // the compiler keeps dozens of precomputed LDS addresses in registers
+        asm volatile("" : "+s"(cb), "+s"(nb));
+        const char *bc = lds + (cb + hs[p]), *bn = lds + (nb + hs[np]);
+        if (p == 0) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) to_mfma_layout(ring[g][2 * b], ring[g][2 * b + 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int y = 0; y < MB; ++y) {
+            const int slot = (n0 + y) % HW;
+            // Every MFMA is written out with its accumulator's register file stated: row blocks 0..15 in AGPRs (all
+            // 256 of them), row block 16 in VGPRs.  Left to choose, the compiler moves accumulators between the two
+            // files inside this loop.
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                if (y < MBA) {
+                    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"
+                                 : "+a"(acc[b][y < MBA ? y : 0])
+                                 : "v"(ring[g][2 * b + p]), "v"(hf[slot]));
+                } else {
+                    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(accv[b]) : "v"(ring[g][2 * b + p]), "v"(hf[slot]));
+                }
+            }
+            hf[slot] = y + HW < MB ? read_h(bc, y + HW) : read_h(bn, y + HW - MB);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // The (tile, slab) sequence of a workgroup is ONE pipeline: hidden_t slabs are the same for every tile (a single
+    // row tile), so slab loads simply wrap around, and ring refills past a tile's last line fetch the first lines of
+    // the workgroup's next tile.  After the last tile both run on into data nobody uses.
+    const int lines = NS;                            // 128-byte lines per W_lm row
+    int T = blockIdx.x;
+    if (T >= ntiles) return;
+    {
+        const int v0 = T * WD_N + wave * 64;
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) w_load(ring[g][j], v0, g, j);
+    }
+    load_h(0, 0);
+    load_h(1, HSLAB);
+    load_h(2, 2 * HSLAB);
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+#pragma unroll
+    for (int y = 0; y < HW; ++y) hf[y] = read_h(lds + hs[0], y);
+    int cb = 0;                                       // byte offset of the LDS buffer of the slab being computed
+
+    for (; T < ntiles; T += gridDim.x) {
+        const int v0 = T * WD_N + wave * 64, v0n = v0 + (int)gridDim.x * WD_N;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+#pragma unroll
+            for (int y = 0; y < MBA; ++y) acc[b][y] = f32x4{0.f, 0.f, 0.f, 0.f};
+            accv[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        // The hand-written MFMAs are invisible to the compiler's hazard handling, and it may sink the zeroing above
+        // to just before an accumulator's first use: make every zeroed register an operand here, then wait.
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+#pragma unroll
+            for (int y = 0; y < MBA; ++y) asm volatile("" : "+a"(acc[b][y]));
+            asm volatile("" : "+v"(accv[b]));
+        }
+        asm volatile("s_nop 7" ::: "memory");
+        auto refill = [&](int g, int line) {         // a burst of 8 loads: 64 rows x one line
+#ifdef WD_ABLATE_NO_W
+            return;
+#endif
+            const bool wrap = line >= lines;
+            int vv = wrap ? v0n : v0;
+            const int ll = wrap ? line - lines : line;
+            // opaque, so that the 8 lane offsets are computed here (a few VALU operations beside hundreds of MFMA
+            // cycles) instead of living in registers - and in scratch memory - across the loop
+            asm volatile("" : "+s"(vv));
+#pragma unroll
+            for (int j = 0; j < 8; ++j) w_load(ring[g][j], vv, ll, j);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+
+        // Whatever the compiler itself has loaded up to here (spilled values) has landed after this wait, which it
+        // knows about: otherwise its own count-down waits for those loads end up inside the loop below, where from
+        // the second trip on they would wait for the kernel's hand-written loads.
+        __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+        // four slabs per trip: slab s + g uses ring group g; the fragment sequence advances by 2 * MB per slab
+        for (int s = 0; s < NS; s += 4) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int sl = s + g;
+                const int nb = cb + HSLAB >= NHB * HSLAB ? 0 : cb + HSLAB;     // buffer of slab sl + 1
+                const int fb = cb == 0 ? (NHB - 1) * HSLAB : cb - HSLAB;         // ... of slab sl - 1 = of slab sl + 3
+                // Loads are issued in the order ... D(s+2) R(s+3) | D(s+3) R(s+4) | ... (D: the HL loads of a hidden_t
+                // slab, after the barrier of slab s; R: the 8 W_lm loads of a line, at the end of slab s) and complete
+                // in that order.  Line sl is needed now: everything up to R(sl) has landed once at most the loads after
+                // it - D(sl) R(sl+1) D(sl+1) R(sl+2) D(sl+2) R(sl+3) - are outstanding.  The registers are operands
+                // of the wait, so nothing that reads them can be scheduled before it.
+                asm volatile("s_waitcnt vmcnt(%8)"
+                             : "+v"(ring[g][0]), "+v"(ring[g][1]), "+v"(ring[g][2]), "+v"(ring[g][3]), "+v"(ring[g][4]),
+                               "+v"(ring[g][5]), "+v"(ring[g][6]), "+v"(ring[g][7])
+                             : "n"(3 * (HL + 8)));
+                piece(g, 0, (2 * g) * MB, cb, cb, 1);
+                // Slab sl + 1 has landed once at most R(sl+2) D(sl+2) R(sl+3) are outstanding.  Every wave has finished
+                // slab sl - 1, so its buffer can take slab sl + 3 (wrapping into the next tile: hidden_t slabs are the
+                // same for every tile).
+                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(HL + 16) : "memory");
+#ifdef WD_ABLATE_NO_H
+                if (a.M < 0)
+#endif
+                load_h(sl + 3 < NS ? sl + 3 : sl + 3 - NS, fb);
+                piece(g, 1, (2 * g + 1) * MB, cb, nb, 0);
+                refill(g, sl + 4);
+                cb = nb;
+            }
+        }
+
+        // the hand-written MFMAs are invisible to the compiler's hazard handling: let the last of them retire
+        // before their accumulators are read
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+        // ---- lane (l16, q4) holds verify row 16y + l16 against vocabulary rows v0 + 16b + 4*q4 + r, ascending in (b, r)
+#pragma unroll
+        for (int y = 0; y < MB; ++y) {
+            const int row = y * 16 + l16, rowc = min(row, a.M - 1);
+            float th = INFINITY;
+            int32_t tk = -1;
+            if (TOPK) {
+                th = a.thr[rowc];
+                tk = a.thr_tok[rowc];
+            }
+            uint32_t klo = 0, khi = 0;
+            if (SAMPLE) {
+                const uint64_t key = a.key[rowc];
+                klo = (uint32_t)key;
+                khi = (uint32_t)(key >> 32);
+            }
+            float bv = -INFINITY;
+            int32_t bi = 0x7fffffff, cn = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int v = v0 + b * 16 + q4 * 4 + r;
+                    float val = y < MBA ? acc[b][y < MBA ? y : 0][r] : accv[b][r];
+                    if (v < a.V) {
+                        if (DUMP && row < a.M) a.dump[(size_t)row * a.V + v] = val;
+                        if (SAMPLE) val = fmaf(val, a.inv_temp, gumbel_noise(klo, khi, (uint32_t)v));
+                        if (val > bv) {      // strict >: the lowest index of the maximum
+                            bv = val;
+                            bi = v;
+                        }
+                        if (TOPK) cn += ranks_before(val, v, th, tk);
+                    }
+                }
+#pragma unroll
+            for (int off = 16; off <= 32; off <<= 1) {
+                const float ov = __shfl_xor(bv, off);
+                const int32_t oi = __shfl_xor(bi, off);
+                if (better(ov, oi, bv, bi)) {
+                    bv = ov;
+                    bi = oi;
+                }
+                if (TOPK) cn += __shfl_xor(cn, off);
+            }
+            if (q4 == 0) {
+                red[wave][row] = Best{bv, bi};
+                if (TOPK) redc[wave][row] = cn;
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        for (int row = threadIdx.x; row < MB * 16 && row < a.M; row += WD_WAVES * 64) {
+            Best best = red[0][row];
+            int32_t cn = TOPK ? redc[0][row] : 0;
+#pragma unroll
+            for (int w = 1; w < WD_WAVES; ++w) {
+                const Best o = red[w][row];
+                if (better(o.v, o.i, best.v, best.i)) best = o;
+                if (TOPK) cn += redc[w][row];
+            }
+            a.part[(size_t)row * a.nblocks + T] = best;
+            if (TOPK) a.cnt[(size_t)row * a.nblocks + T] = cn;
+        }
+        // `red` is rewritten only after the barriers of the next tile.  The slab waits count this wave's loads in
+        // issue order, and stores need not retire in that order: let the stores above retire here.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+}
+
+template <int MB>
+hipError_t launch_wide(const LmHeadArgs &a, int num_cus, hipStream_t s)
+{
+    const int ntiles = (a.V + WD_N - 1) / WD_N;
+    const int grid = ntiles < num_cus ? ntiles : num_cus;
+    const dim3 g(grid), b(WD_WAVES * 64);
+    if (a.dump) hipLaunchKernelGGL((k_lm_head_wide<MB, true, false, false>), g, b, 0, s, a, ntiles);
+    else if (a.thr) hipLaunchKernelGGL((k_lm_head_wide<MB, false, true, false>), g, b, 0, s, a, ntiles);
+    else if (a.key) hipLaunchKernelGGL((k_lm_head_wide<MB, false, false, true>), g, b, 0, s, a, ntiles);
+    else hipLaunchKernelGGL((k_lm_head_wide<MB, false, false, false>), g, b, 0, s, a, ntiles);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool lm_head_wide_supports(int M, int V, int d)
+{
+    if (M <= 128 || M > WD_MAXB * 16 || V <= 0 || d < 256 || d % 256 != 0) return false;
+    if ((uint64_t)V * d * 2 >= (1ull << 32) || (uint64_t)M * d * 2 >= (1ull << 32)) return false;
+    return V < (1 << 24) && d * 2 < (1 << 24);
+}
+
+int lm_head_wide_blocks(int V) { return (V + WD_N - 1) / WD_N; }
+
+hipError_t lm_head_wide_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s)
+{
+    if (a.M <= 0) return hipSuccess;
+    switch ((a.M + 15) / 16) {
+        case 9: return launch_wide<9>(a, num_cus, s);
+        case 10: return launch_wide<10>(a, num_cus, s);
+        case 11: return launch_wide<11>(a, num_cus, s);
+        case 12: return launch_wide<12>(a, num_cus, s);
+        case 13: return launch_wide<13>(a, num_cus, s);
+        case 14: return launch_wide<14>(a, num_cus, s);
+        case 15: return launch_wide<15>(a, num_cus, s);
+        case 16: return launch_wide<16>(a, num_cus, s);
+        case 17: return launch_wide<17>(a, num_cus, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace aj

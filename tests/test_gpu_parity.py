@@ -9,7 +9,7 @@ from parity import compare, make_inputs, oracle_greedy, parity_case, run_gpu
 pytestmark = pytest.mark.gpu
 
 TINY = wl.WORKLOADS["tiny_f32"]
-KERNELS_BF16 = [1, 2, 3, 4, 5, 6, 7] # AJ_KERNEL_TILE, _STREAM, _BIG, _TALL, _PAIR, _PAIR9, _RESIDENT (forced); 0 = AUTO is covered too
+KERNELS_BF16 = [1, 2, 3, 4, 5, 6, 7, 8] # AJ_KERNEL_TILE, _STREAM, _BIG, _TALL, _PAIR, _PAIR9, _RESIDENT, _WIDE (forced); 0 = AUTO is covered too
 
 
 def _skip_unless_supported(w, kernel):
@@ -62,6 +62,9 @@ def test_tiny_f32_workload_with_all_logits():
     dict(B=1, K=64, d_t=2048, d_d=64, V=140000),       # M=65; more vocabulary than one pass of 256 workgroups holds
     dict(B=4, K=31, d_t=768, d_d=64, V=3001),          # M=128: all eight row blocks, three k slabs
     dict(B=7, K=15, d_t=256, d_d=64, V=530),           # M=112, a single k slab, a ragged last vocabulary block
+    dict(B=8, K=32, d_t=1024, d_d=64, V=3000),         # M=264: 17 row blocks of the wide kernel (one in VGPRs)
+    dict(B=3, K=42, d_t=256, d_d=64, V=70000),         # M=129: 9 row blocks, one trip of four slabs, 274 tiles on 256 workgroups
+    dict(B=8, K=31, d_t=512, d_d=64, V=1000),          # M=256: 16 row blocks
 ])
 def test_bf16_shapes_all_kernels(kernel, shape):
     import torch
@@ -276,11 +279,11 @@ def test_profile_events_and_kernel_names():
     with pytest.raises(aj.AjError):
         aj.aj_profile_read(plain)
     aj.aj_destroy(plain)
-    for M_B, d_t, name in ((8, 4096, "lm_head_pair_bf16"), (8, 4096 + 64, "lm_head_big_bf16"), (4, 4096, "lm_head_resident_bf16"), (4, 4096 + 128, "lm_head_stream_bf16"), (5, 4096, "lm_head_pair_bf16"),
+    for M_B, d_t, name in ((8, 4096, "lm_head_pair_bf16"), (8, 4096 + 64, "lm_head_big_bf16"), (4, 4096, "lm_head_resident_bf16"), (4, 4096 + 128, "lm_head_stream_bf16"), (5, 4096, "lm_head_wide_bf16"), (5, 4096 + 128, "lm_head_big_bf16"),
                            (4, 4096 + 8, "lm_head_tile_bf16"), (9, 4096, "lm_head_pair9_bf16"), (10, 4096, "lm_head_tall_bf16"),
                            (33, 4096, "lm_head_pair9_bf16"), (33, 4096 + 64, "lm_head_tall_bf16"),
                            (260, 4096, "lm_head_pair_bf16")):
-        hh = aj.aj_create(M_B, 31, d_t, 64, 4096, aj.AJ_BF16)     # 256, 256, 128, 128, 160, 128, 288, 320, 1056, 1056, 8320 verify rows
+        hh = aj.aj_create(M_B, 31, d_t, 64, 4096, aj.AJ_BF16)     # 256, 256, 128, 128, 160, 160, 128, 288, 320, 1056, 1056, 8320 verify rows
         assert aj.aj_kernel_name(hh) == name, (M_B, aj.aj_kernel_name(hh))
         aj.aj_destroy(hh)
 
@@ -292,6 +295,7 @@ def test_profile_events_and_kernel_names():
     (5, dict(B=9, K=31, d_t=768, d_d=64, V=5000)),
     (6, dict(B=9, K=31, d_t=768, d_d=64, V=5000)),
     (7, dict(B=3, K=31, d_t=768, d_d=64, V=20000)),
+    (8, dict(B=8, K=32, d_t=768, d_d=64, V=70000)),
 ])
 def test_run_to_run_bit_identical(kernel, shape):
     w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="det", p_match=0.5, **shape)

@@ -97,7 +97,7 @@ def test_tiny_f32():
     assert (gpu[w.V]["out_len"] == w.K).all()
 
 
-@pytest.mark.parametrize("kernel", [0, 1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("kernel", [0, 1, 2, 3, 4, 5, 6, 7, 8])
 @pytest.mark.parametrize("shape", [
     dict(B=1, K=16, d_t=4096, d_d=64, V=5003),         # 16-row streaming kernel, ragged vocabulary
     dict(B=2, K=15, d_t=384, d_d=64, V=20000),         # streaming regime at another hidden size
@@ -105,6 +105,7 @@ def test_tiny_f32():
     dict(B=3, K=16, d_t=1024, d_d=64, V=2500),         # general 128x128 kernel
     dict(B=9, K=31, d_t=512, d_d=64, V=3001),          # M=288: 256-row kernels (2 row tiles) and the 8-wave one
     dict(B=1, K=64, d_t=1024, d_d=64, V=3001),         # M=65: accumulator-resident kernel, five row blocks
+    dict(B=8, K=32, d_t=512, d_d=64, V=3001),          # M=264: the wide kernel's 17 row blocks
     dict(B=20, K=31, d_t=256, d_d=64, V=1100),         # M=640
     dict(B=4, K=24, d_t=512, d_d=64, V=3000),          # M=100: the 128-row streaming tile
 ])
