@@ -93,6 +93,8 @@ def bench_workload(args, name, cache, cpu_seconds):
         keys = np.random.default_rng(seed).integers(0, 2**63, size=(w.B, w.K + 1), dtype=np.int64)
         d_key = torch.from_numpy(keys).cuda()
     extra = aj.AJ_FLAG_TOPK if topk else 0
+    if args.fused_judge:
+        extra |= aj.AJ_FLAG_FUSED_JUDGE
     h = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, w.dtype_code, 1, extra, args.kernel, w_dtype)
     hp = aj.aj_create(w.B, w.K, w.d_t, w.d_d, w.V, w.dtype_code, 1, aj.AJ_FLAG_PROFILE | extra, args.kernel, w_dtype)
 
@@ -191,6 +193,7 @@ def bench_workload(args, name, cache, cpu_seconds):
                    "verify_rows": w.M, "tau": w.tau, "p_match": w.p_match, "seed": seed,
                    "draft_tokens": draft_from,
                    **({"w_dtype": "fp8_e4m3"} if fp8 else {}),
+                   **({"fused_judge": True} if args.fused_judge else {}),
                    **({"mode": "topk", "top_k": args.top_k} if topk else {}),
                    **({"mode": "sample", "inv_temperature": args.inv_temperature} if sample else {})},
         "verify_rows_per_s": w.M / (ms_per_step * 1e-3),
@@ -253,6 +256,9 @@ def main():
     ap.add_argument("--w-dtype", choices=["same", "fp8"], default="same",
                     help="fp8: W_lm stored as OCP FP8 E4M3; not the metric's configuration, which is bf16")
     ap.add_argument("--top-k", type=int, default=8)
+    ap.add_argument("--fused-judge", action="store_true",
+                    help="AJ_FLAG_FUSED_JUDGE: the judge's target half as one more row of the LM-head pass (up to 128 "
+                         "verify rows); off in the metric's configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="instead of the benchmark: a plain device copy of 1 GiB, repeated --steps times "

@@ -67,7 +67,13 @@ typedef enum {
 enum {
     AJ_FLAG_DEBUG = 1,   /* keep per-slot judge scores for aj_debug_ptrs */
     AJ_FLAG_PROFILE = 2, /* record HIP events around the LM-head kernel (aj_profile_read) */
-    AJ_FLAG_TOPK = 4     /* also allocate the workspace of aj_verify_topk */
+    AJ_FLAG_TOPK = 4,    /* also allocate the workspace of aj_verify_topk */
+    AJ_FLAG_FUSED_JUDGE = 8 /* the judge's target half, clf_w[0:d_t] . hidden_t[r], is computed for EVERY verify row
+                               inside the LM-head pass, as one more row of the LM-head operand (Section 3.2, "Classifier
+                               model": the regression can be fused with the LM head layer); at a mismatch the tail then adds
+                               only the draft half and the bias.  Same results within the score tolerance.  Served by the
+                               kernel for up to 128 verify rows at d_t % 256 == 0 with bf16 weights (AJ_EINVAL otherwise);
+                               aj_verify_sampled and aj_verify_topk calls on such a handle compute the judge as usual. */
 };
 
 enum { AJ_W_SAME = 0, AJ_W_FP8_E4M3 = 1 };

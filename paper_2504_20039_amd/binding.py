@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("AJ_LIBRARY") or os.path.join(_HERE, "libaj.so")
 
 AJ_F32, AJ_BF16 = 0, 1
-AJ_FLAG_DEBUG, AJ_FLAG_PROFILE, AJ_FLAG_TOPK = 1, 2, 4
+AJ_FLAG_DEBUG, AJ_FLAG_PROFILE, AJ_FLAG_TOPK, AJ_FLAG_FUSED_JUDGE = 1, 2, 4, 8
 AJ_W_SAME, AJ_W_FP8_E4M3 = 0, 1
 AJ_KERNEL_AUTO, AJ_KERNEL_TILE, AJ_KERNEL_STREAM, AJ_KERNEL_BIG, AJ_KERNEL_TALL, AJ_KERNEL_PAIR, AJ_KERNEL_PAIR9, AJ_KERNEL_RESIDENT, AJ_KERNEL_WIDE = 0, 1, 2, 3, 4, 5, 6, 7, 8
 

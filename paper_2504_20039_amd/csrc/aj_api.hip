@@ -22,6 +22,7 @@ struct aj_handle {
     float *maxlogit;
     float *score;  // [2][B][K] or nullptr
     uint8_t *rej;  // [B][K] rejected-slot flags (tail kernels' split form)
+    float *zt;     // [M] fused judge row's logits (AJ_FLAG_FUSED_JUDGE)
     // top-K baseline workspace (AJ_FLAG_TOPK)
     int32_t *cnt;      // [M][nblocks]
     float *thr;        // [M]
@@ -64,6 +65,7 @@ static void free_all(aj_handle *h)
     if (h->maxlogit) (void)hipFree(h->maxlogit);
     if (h->score) (void)hipFree(h->score);
     if (h->rej) (void)hipFree(h->rej);
+    if (h->zt) (void)hipFree(h->zt);
     if (h->cnt) (void)hipFree(h->cnt);
     if (h->thr) (void)hipFree(h->thr);
     if (h->thr_tok) (void)hipFree(h->thr_tok);
@@ -89,6 +91,7 @@ static int plan_handle(const aj_config &c, aj_handle *h)
     // vocabulary indices go through 24-bit multiplies (tile offsets, the sampling generator's first step)
     if (c.V >= (1 << 24)) return AJ_EINVAL;
 
+    if (c.flags & ~(AJ_FLAG_DEBUG | AJ_FLAG_PROFILE | AJ_FLAG_TOPK | AJ_FLAG_FUSED_JUDGE)) return AJ_EINVAL;
     h->cfg = c;
     h->M = c.B * (c.K + 1);
     hipError_t e = hipGetDevice(&h->device);
@@ -101,7 +104,7 @@ static int plan_handle(const aj_config &c, aj_handle *h)
     if (c.w_dtype == AJ_W_FP8_E4M3) {
         // FP8 weights: the two W_lm-streaming kernels only (up to 128 verify rows), and no top-K baseline (its
         // pre-pass reads W_lm rows)
-        if (c.dtype != AJ_BF16 || (c.flags & AJ_FLAG_TOPK)) return AJ_EINVAL;
+        if (c.dtype != AJ_BF16 || (c.flags & (AJ_FLAG_TOPK | AJ_FLAG_FUSED_JUDGE))) return AJ_EINVAL;
         const bool s16 = (c.kernel == AJ_KERNEL_AUTO || c.kernel == AJ_KERNEL_STREAM) &&
                          lm_head_stream16_fp8w_supports(h->M, c.V, c.d_t);
         const bool res = (c.kernel == AJ_KERNEL_AUTO || c.kernel == AJ_KERNEL_RESIDENT) &&
@@ -117,7 +120,7 @@ static int plan_handle(const aj_config &c, aj_handle *h)
             h->nblocks = lm_head_resident_blocks(c.V, h->num_cus);
         }
     } else if (c.dtype == AJ_F32) {
-        if (c.kernel != AJ_KERNEL_AUTO) {
+        if (c.kernel != AJ_KERNEL_AUTO || (c.flags & AJ_FLAG_FUSED_JUDGE)) {
             return AJ_EINVAL;
         }
         h->variant = -1;
@@ -176,6 +179,12 @@ static int plan_handle(const aj_config &c, aj_handle *h)
             return AJ_EINVAL;   // a forced variant that cannot run this shape
         }
         if (v == AJ_KERNEL_TILE && lm_head_tile_blocks(c.V) > 65535) return AJ_EINVAL;   // gridDim.y
+        if ((c.flags & AJ_FLAG_FUSED_JUDGE) && h->M > 0) {
+            // the fused judge row lives in the accumulator-resident kernel
+            if (c.kernel != AJ_KERNEL_AUTO && c.kernel != AJ_KERNEL_RESIDENT) return AJ_EINVAL;
+            if (!lm_head_resident_supports(h->M, c.V, c.d_t, false)) return AJ_EINVAL;
+            v = AJ_KERNEL_RESIDENT;
+        }
         h->variant = v;
         h->stream16 = v == AJ_KERNEL_STREAM && lm_head_stream16_supports(h->M, c.V, c.d_t);
         h->nblocks = v == AJ_KERNEL_TILE ? lm_head_tile_blocks(c.V)
@@ -209,6 +218,8 @@ extern "C" int aj_create(const aj_config *cfg, aj_handle **out)
                   hipMalloc(&h->rej, (size_t)h->M) == hipSuccess;
         if (ok && (c.flags & AJ_FLAG_DEBUG))
             ok = hipMalloc(&h->score, (size_t)2 * c.B * c.K * sizeof(float)) == hipSuccess;
+        if (ok && (c.flags & AJ_FLAG_FUSED_JUDGE))
+            ok = hipMalloc(&h->zt, (size_t)h->M * sizeof(float)) == hipSuccess;
         if (ok && (c.flags & AJ_FLAG_TOPK))
             ok = hipMalloc(&h->cnt, np * sizeof(int32_t)) == hipSuccess &&
                  hipMalloc(&h->thr, (size_t)h->M * sizeof(float)) == hipSuccess &&
@@ -249,7 +260,8 @@ extern "C" int aj_destroy(aj_handle *h)
 }
 
 static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void *W_lm, float *dump, hipStream_t s,
-                                 bool topk = false, const uint64_t *key = nullptr, float inv_temp = 1.f)
+                                 bool topk = false, const uint64_t *key = nullptr, float inv_temp = 1.f,
+                                 const void *judge_w = nullptr)
 {
     LmHeadArgs a;
     a.H = hidden_t;
@@ -265,6 +277,8 @@ static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void 
     a.cnt = topk ? h->cnt : nullptr;
     a.key = key;
     a.inv_temp = inv_temp;
+    a.judge_w = judge_w;
+    a.zt = judge_w ? h->zt : nullptr;
     if (h->variant < 0) return lm_head_f32(a, s);
     if (h->variant == AJ_KERNEL_TILE) return lm_head_tile_bf16(a, s);
     if (h->variant == AJ_KERNEL_RESIDENT)
@@ -299,7 +313,11 @@ static int verify_common(aj_handle *h, const void *hidden_t, const void *hidden_
     const int slot = (int)(h->calls % 64);
     hipError_t e;
     if (prof && (e = hipEventRecord(h->ev[slot][0], s)) != hipSuccess) return hip_fail(e);
-    if ((e = launch_lm_head(h, hidden_t, W_lm, nullptr, s, false, key, inv_temp)) != hipSuccess) return hip_fail(e);
+    // fused judge row: greedy chains and trees on a handle created for it (the sampling variant computes the judge
+    // in the tail, as usual)
+    const bool fused = h->zt && !key && h->variant == AJ_KERNEL_RESIDENT && !h->fp8w;
+    if ((e = launch_lm_head(h, hidden_t, W_lm, nullptr, s, false, key, inv_temp, fused ? clf_w : nullptr)) != hipSuccess)
+        return hip_fail(e);
     if (prof && (e = hipEventRecord(h->ev[slot][1], s)) != hipSuccess) return hip_fail(e);
     if (prof) h->calls++;
 
@@ -322,6 +340,7 @@ static int verify_common(aj_handle *h, const void *hidden_t, const void *hidden_
     t.zthr = tau <= 0.f ? -INFINITY : (tau >= 1.f ? INFINITY : (float)log((double)tau / (1.0 - (double)tau)));
     t.t_star = h->t_star;
     t.maxlogit = h->maxlogit;
+    t.zt = fused ? h->zt : nullptr;
     t.score = h->score;
     t.rej = h->rej;
     t.out_len = out_len;

@@ -35,6 +35,10 @@ struct LmHeadArgs {
     // logit * inv_temp + Gumbel noise(key, vocabulary index) instead of the logit
     const uint64_t *key;    // [M]
     float inv_temp;
+    // fused judge row (nullptr otherwise; accumulator-resident kernel only): judge_w = clf_w[0:d], one more row of
+    // the LM-head operand that takes no part in the maximum; its logits go to zt [M]
+    const void *judge_w;
+    float *zt;
 };
 
 __device__ __forceinline__ bool better(float v, int32_t i, float bv, int32_t bi)
@@ -142,6 +146,7 @@ struct TailArgs {
     float clf_b, zthr;      // zthr = log(tau/(1-tau)), -inf/+inf at the ends
     int32_t *t_star;        // [M] out
     float *maxlogit;        // [M] out
+    const float *zt;        // [M] target half of the judge logit of every verify row (fused judge row), or nullptr
     float *score;           // [B][K] out or nullptr
     uint8_t *rej;           // [B][K] workspace of the split form: 1 = slot rejected (nullptr: one-launch form only)
     int32_t *out_len, *out_tok;

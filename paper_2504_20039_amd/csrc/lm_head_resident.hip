@@ -37,7 +37,7 @@ constexpr int RS_NBW = 4;                       // 16-row vocabulary blocks per 
 constexpr int RS_KS = 256;                      // k elements per slab
 constexpr int RS_HROW = RS_KS * 2;              // bytes of a hidden_t row per slab
 
-template <int MB, bool FP8W, bool DUMP, bool TOPK, bool SAMPLE>
+template <int MB, bool FP8W, bool DUMP, bool TOPK, bool SAMPLE, bool JUDGE = false>
 __global__ __launch_bounds__(RS_WAVES * 64) void k_lm_head_resident(LmHeadArgs a, int passes, int rot_step)
 {
     constexpr int HSLAB = MB * 16 * RS_HROW;                 // bytes of a hidden_t slab in LDS
@@ -98,7 +98,15 @@ __global__ __launch_bounds__(RS_WAVES * 64) void k_lm_head_resident(LmHeadArgs a
     const uint32_t cbyte = (uint32_t)(q4 + 4 * (l16 >> 3)) * 16u;
     // load j = 2*pr + h of the visit to block blk of the wave whose first row is v0; slab_off: byte offset of the
     // slab in a row (uniform).  Rows are clamped into the vocabulary (their logits are never looked at).
+    // JUDGE: the judge's target weights clf_w[0:d] are one more vocabulary row, the first of the 16-row block that
+    // follows the vocabulary's last one (Section 3.2: the regression fused with the LM head); all 16 lanes rows of that
+    // block read the same row, whose logits go to a.zt instead of the maximum.
+    const int vj = (a.V + 15) / 16 * 16;
+    const __amdgpu_buffer_rsrc_t jres =
+        __builtin_amdgcn_make_buffer_rsrc((void *)(JUDGE ? a.judge_w : a.W), 0, (int)wrow, 0x00020000);
     auto w_load = [&](int v0, int slab_off, int blk, int j) {
+        if (JUDGE && v0 + blk * 16 == vj)       // wave-uniform
+            return __builtin_amdgcn_raw_buffer_load_b128(jres, (int)cbyte + (j >> 1) * 128, slab_off, 0);
         const int row = min(v0 + blk * 16 + (j & 1) * 8 + r8, a.V - 1);
         return __builtin_amdgcn_raw_buffer_load_b128(wres, (int)(__umul24(row, wrow) + cbyte) + (j >> 1) * 128,
                                                      slab_off, 2 /* nt */);
@@ -127,7 +135,7 @@ __global__ __launch_bounds__(RS_WAVES * 64) void k_lm_head_resident(LmHeadArgs a
     }
 
     // a wave whose first row lies beyond the vocabulary in pass 0 never computes: it only helps to stage hidden_t
-    const bool active = gw * (RS_NBW * 16) < a.V;
+    const bool active = gw * (RS_NBW * 16) < (JUDGE ? vj + 16 : a.V);
 
     int wcur, wnxt;
     int scur = slab_of(0) * WSEG, snxt = 0;          // byte offset of the slab in a W_lm row
@@ -237,6 +245,7 @@ __global__ __launch_bounds__(RS_WAVES * 64) void k_lm_head_resident(LmHeadArgs a
                 int32_t bi = 0x7fffffff, cn = 0;
 #pragma unroll
                 for (int b = 0; b < RS_NBW; ++b) {
+                    if (JUDGE && v0 + b * 16 == vj && q4 == 0 && row < a.M) a.zt[row] = acc[b][y][0];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int v = v0 + b * 16 + q4 * 4 + r;
@@ -301,8 +310,9 @@ int resident_grid(int V, int num_cus)
 template <int MB, bool FP8W>
 hipError_t launch_resident(const LmHeadArgs &a, int num_cus, hipStream_t s)
 {
-    const int grid = resident_grid(a.V, num_cus);
-    const int nb = (a.V + 15) / 16, per_pass = grid * RS_WAVES * RS_NBW;
+    const bool judge = a.judge_w != nullptr;
+    const int grid = resident_grid(a.V + 16, num_cus);      // = lm_head_resident_blocks: one partial per workgroup
+    const int nb = (a.V + 15) / 16 + (judge ? 1 : 0), per_pass = grid * RS_WAVES * RS_NBW;
     const int passes = (nb + per_pass - 1) / per_pass;
     // workgroups start at different slabs (5 apart): at any moment the chip reads many k offsets of W_lm, not the
     // same column of every row
@@ -311,6 +321,7 @@ hipError_t launch_resident(const LmHeadArgs &a, int num_cus, hipStream_t s)
     if (a.dump) hipLaunchKernelGGL((k_lm_head_resident<MB, FP8W, true, false, false>), g, b, 0, s, a, passes, rot_step);
     else if (a.thr) hipLaunchKernelGGL((k_lm_head_resident<MB, FP8W, false, true, false>), g, b, 0, s, a, passes, rot_step);
     else if (a.key) hipLaunchKernelGGL((k_lm_head_resident<MB, FP8W, false, false, true>), g, b, 0, s, a, passes, rot_step);
+    else if (judge && !FP8W) hipLaunchKernelGGL((k_lm_head_resident<MB, false, false, false, false, true>), g, b, 0, s, a, passes, rot_step);
     else hipLaunchKernelGGL((k_lm_head_resident<MB, FP8W, false, false, false>), g, b, 0, s, a, passes, rot_step);
     return hipGetLastError();
 }
@@ -341,7 +352,8 @@ bool lm_head_resident_supports(int M, int V, int d, bool fp8w)
     return V < (1 << 24) && d * 2 < (1 << 24);
 }
 
-int lm_head_resident_blocks(int V, int num_cus) { return resident_grid(V, num_cus); }
+// V + 16: room for the fused judge row's block, whether it is used or not (a neutral partial costs nothing)
+int lm_head_resident_blocks(int V, int num_cus) { return resident_grid(V + 16, num_cus); }
 
 hipError_t lm_head_resident_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s)
 {

@@ -119,7 +119,9 @@ __global__ __launch_bounds__(TAIL_WAVES * 64) void k_verify_tail(TailArgs a)
         bool r = false;
         if (mis) {
             const size_t row = (size_t)b * R + (TREE ? (a.feat_offset ? j + 1 : prow) : j + a.feat_offset);
-            float acc = dot_part<BF16>((const char *)a.hidden_t + row * a.d_t * es, a.clf_w, a.d_t, lane);
+            // target half: from the LM-head pass (fused judge row), else a dot product here
+            float acc = a.zt ? (lane == 0 ? a.zt[row] : 0.f)
+                             : dot_part<BF16>((const char *)a.hidden_t + row * a.d_t * es, a.clf_w, a.d_t, lane);
             if (a.d_d > 0)
                 acc += dot_part<BF16>((const char *)a.hidden_d + row * a.d_d * es,
                                       (const char *)a.clf_w + (size_t)a.d_t * es, a.d_d, lane);
@@ -231,7 +233,8 @@ __global__ __launch_bounds__(ROWS_PER_WG * 64) void k_tail_rows(TailArgs a)
     bool r = false;
     if (mis) {
         const size_t frow = (size_t)row + a.feat_offset;     // same window: j + feat_offset <= K
-        float acc = dot_part<BF16, 8>((const char *)a.hidden_t + frow * a.d_t * es, a.clf_w, a.d_t, lane);
+        float acc = a.zt ? (lane == 0 ? a.zt[frow] : 0.f)
+                         : dot_part<BF16, 8>((const char *)a.hidden_t + frow * a.d_t * es, a.clf_w, a.d_t, lane);
         if (a.d_d > 0)
             acc += dot_part<BF16, 8>((const char *)a.hidden_d + frow * a.d_d * es,
                                      (const char *)a.clf_w + (size_t)a.d_t * es, a.d_d, lane);

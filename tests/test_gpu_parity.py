@@ -174,6 +174,37 @@ def test_target_only_judge():
         parity_case(w, 9, tau=tau)
 
 
+@pytest.mark.parametrize("shape", [
+    dict(B=1, K=32, d_t=1024, d_d=256, V=5000),        # 33 rows; the judge row is the first of a wave's block
+    dict(B=4, K=31, d_t=512, d_d=64, V=3001),          # 128 rows; ragged vocabulary: the judge block follows a partial one
+    dict(B=3, K=15, d_t=256, d_d=0, V=530),            # target-only features: the judge is the fused row alone
+    dict(B=1, K=64, d_t=768, d_d=128, V=140000),       # several passes over the vocabulary; the judge block in the last
+    dict(B=2, K=7, d_t=2048, d_d=64, V=16352),         # the vocabulary fills 511 of 512 blocks of one pass
+])
+def test_fused_judge_row(shape):
+    """AJ_FLAG_FUSED_JUDGE: the judge's target half comes out of the LM-head pass as one more operand row; scores within
+    1e-3 of the oracle on every mismatching slot, outcomes bit-exact, for both feature rows and a tau sweep."""
+    import paper_2504_20039_amd as aj
+    w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="fused", p_match=0.4, **shape)
+    x = make_inputs(w, 21)
+    greedy = oracle_greedy(x)
+    draft = wl.draft_tokens(w, 21, greedy[0])
+    for feat_offset in (1, 0):
+        for tau in (0.0, 0.4, 0.7, 1.0):
+            gpu = run_gpu(x, draft, tau, feat_offset, flags=aj.AJ_FLAG_DEBUG | aj.AJ_FLAG_FUSED_JUDGE, repeat=2)
+            assert gpu["kernel"] == "lm_head_resident_bf16"
+            rep = compare(x, draft, tau, greedy, gpu, feat_offset)
+            plain = run_gpu(x, draft, tau, feat_offset)
+            assert np.array_equal(plain["out_len"], gpu["out_len"]) or rep["near_thr_windows"] > 0
+    # shapes the fused row is not built for are refused at create
+    for bad in (dict(B=8, K=32), dict(d_t=w.d_t + 64)):
+        a = dict(B=w.B, K=w.K, d_t=w.d_t)
+        a.update(bad)
+        with pytest.raises(aj.AjError) as e:
+            aj.aj_create(a["B"], a["K"], a["d_t"], w.d_d, w.V, aj.AJ_BF16, 1, aj.AJ_FLAG_FUSED_JUDGE)
+        assert e.value.status == -1
+
+
 def test_long_window():
     w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="long", B=2, K=200, d_t=128, d_d=64, V=300, p_match=0.9,
                   clf_b=-2.0)
