@@ -188,7 +188,9 @@ int aj_verify_sampled(aj_handle *h, const void *hidden_t, const void *hidden_d, 
  * in registers, with the logit of the row's draft token:
  *   rank[b][j] = number of vocabulary entries ordered before draft_tok[b][j] in row (b, j)
  *                (larger logit first, lower index first among equal logits; rank 0 = greedy token);
- *                V for a token outside [0, V)
+ *                V for a token outside [0, V).  The token's own logit is computed by a separate dot product,
+ *                so entries within fp32 rounding of it (~1e-6 relative) may fall on either side; the greedy
+ *                token is given rank 0 outright
  *   out_len[b] = first slot with rank >= top_k (K if none), out_tok[b] = greedy token of that row.
  * top_k = 1 is plain greedy verification, top_k >= V accepts every valid token.
  * Needs AJ_FLAG_TOPK at aj_create (AJ_ESTATE otherwise); AJ_EINVAL on null / misaligned pointers or

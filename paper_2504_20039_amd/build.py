@@ -27,8 +27,9 @@ def _stale(target, deps):
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = False, verbose: bool = False) -> str:
-    """Compile every csrc/*.hip to an object and link them into libaj.so."""
+def build(force: bool = False, verbose: bool = False, check: bool = False) -> str:
+    """Compile every csrc/*.hip to an object and link them into libaj.so.  check: also verify the generated code of the
+    hand-scheduled kernels (check_isa.py); raises if a loop holds spills, register-file moves or foreign waits."""
     os.makedirs(OBJDIR, exist_ok=True)
     headers = glob.glob(os.path.join(CSRC, "*.h")) + [os.path.join(HERE, "..", "include", "aj.h")]
     jobs = []
@@ -52,8 +53,11 @@ def build(force: bool = False, verbose: bool = False) -> str:
         list(ex.map(run, jobs))
     if force or jobs or _stale(LIB, objs):
         run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
+    if check:
+        from . import check_isa
+        check_isa.check(HIPCC, FLAGS, verbose)
     return LIB
 
 
 if __name__ == "__main__":
-    print(build(force=True, verbose=True))
+    print(build(force=True, verbose=True, check=True))

@@ -130,16 +130,15 @@ static int plan_handle(const aj_config &c, aj_handle *h)
         int v = c.kernel;
         if (v == AJ_KERNEL_AUTO) {
             // W_lm-streaming kernels up to 128 verify rows: the 16-row-tile kernel with hidden_t in registers
-            // (<= 32 rows, d_t = 2048 or 4096), else 128-vocabulary tiles of 32, 64 or 128 rows with a running
-            // maximum (5.7 TB/s at 34..64 rows, 4.8 at 65..128, against 4.4 of a padded 256-row tile).  Above
-            // that, the large-tile
-            // kernel with the lowest cost = padded row count x a per-row factor measured on one device against
-            // the 256-row whole-line kernel (PAIR = 1): its 288-row variant 1.06, the 256-row kernel with
-            // 64-byte pieces 1.10, the 8-wave 288/320-row kernel 1.15.  Padded rows are wasted MFMA work, and a
-            // batch of 257..320 rows in ONE row tile reads W_lm from HBM only once.  Below 256 rows a single
-            // padded tile still wins over the general 128 x 128 kernel: the step is bound by streaming W_lm,
-            // which these pipelines do at 4.2-4.9 TB/s against 2.2-3.8 (34..255 rows, same device).  The general
-            // kernel serves what is left: hidden sizes that are not a multiple of 32.
+            // (<= 32 rows, d_t = 2048 or 4096), else the kernel that keeps the logits in registers (d_t % 256 == 0), else
+            // 128-vocabulary tiles of 32, 64 or 128 rows with a running maximum.  129..240 rows: the wide kernel.
+            // Above that, the large-tile kernel with the lowest cost = padded row count x a per-row factor against the
+            // 256-row whole-line kernel (PAIR = 1).  Measured on 1056 rows at d_t = 4096 / 8192 and 8320 rows at 8192
+            // (one device; devices differ by about 5 %): the 288-row variant 1.09 / 1.05 / 1.03, the 256-row kernel
+            // with 64-byte pieces 1.11 / 1.09 / 1.10, the 8-wave 288/320-row kernel 1.24 / 1.26 / 1.19; constants
+            // 1.06, 1.10, 1.20.  Padded rows are wasted MFMA work, and a batch of 257..320 rows in ONE row tile reads
+            // W_lm from HBM only once.  The general kernel serves what is left: hidden sizes that are not a multiple
+            // of 32.
             if (lm_head_stream16_supports(h->M, c.V, c.d_t)) {
                 v = AJ_KERNEL_STREAM;
             } else if (lm_head_resident_supports(h->M, c.V, c.d_t, false)) {
@@ -159,7 +158,7 @@ static int plan_handle(const aj_config &c, aj_handle *h)
                     {AJ_KERNEL_BIG, lm_head_mfma_supports(AJ_KERNEL_BIG, h->M, c.V, c.d_t),
                      1.10 * lm_head_mfma_padded_rows(AJ_KERNEL_BIG, h->M)},
                     {AJ_KERNEL_TALL, lm_head_mfma_supports(AJ_KERNEL_TALL, h->M, c.V, c.d_t),
-                     1.15 * lm_head_mfma_padded_rows(AJ_KERNEL_TALL, h->M)},
+                     1.20 * lm_head_mfma_padded_rows(AJ_KERNEL_TALL, h->M)},
                 };
                 v = AJ_KERNEL_TILE;
                 double best = 0.0;

@@ -121,14 +121,15 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
         // the compiler keeps dozens of precomputed LDS addresses in registers
         asm volatile("" : "+s"(cb), "+s"(nb));
         const char *bc = lds + (cb + hs[p]), *bn = lds + (nb + hs[np]);
-        if (p == 0) {
-#pragma unroll
-            for (int b = 0; b < 4; ++b) to_mfma_layout(ring[g][2 * b], ring[g][2 * b + 1]);
-            __builtin_amdgcn_sched_barrier(0);
-        }
+        // In the second piece of a line the NEXT line's registers are brought to the MFMA layout, one block after
+        // every FS row blocks, in the shadow of the MFMAs (with one wave per SIMD nothing else covers VALU work; as a
+        // block of 48 moves before the first piece it left the matrix pipe idle for a tenth of the slab)
+        constexpr int FS = MB / 4;
+        const int gn = (g + 1) & 3;
 #pragma unroll
         for (int y = 0; y < MB; ++y) {
             const int slot = (n0 + y) % HW;
+            if (p == 1 && y % FS == 0 && y / FS < 4) to_mfma_layout(ring[gn][2 * (y / FS)], ring[gn][2 * (y / FS) + 1]);
             // Every MFMA is written out with its accumulator's register file stated: row blocks 0..15 in AGPRs (all
             // 256 of them), row block 16 in VGPRs.  Left to choose, the compiler moves accumulators between the two
             // files inside this loop.
@@ -163,7 +164,14 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
     load_h(0, 0);
     load_h(1, HSLAB);
     load_h(2, 2 * HSLAB);
-    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    // (the first line's registers are operands of the wait: the moves below must not be scheduled before it)
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier"
+                 : "+v"(ring[0][0]), "+v"(ring[0][1]), "+v"(ring[0][2]), "+v"(ring[0][3]), "+v"(ring[0][4]), "+v"(ring[0][5]),
+                   "+v"(ring[0][6]), "+v"(ring[0][7])
+                 :
+                 : "memory");
+#pragma unroll
+    for (int b = 0; b < 4; ++b) to_mfma_layout(ring[0][2 * b], ring[0][2 * b + 1]);
 #pragma unroll
     for (int y = 0; y < HW; ++y) hf[y] = read_h(lds + hs[0], y);
     int cb = 0;                                       // byte offset of the LDS buffer of the slab being computed
@@ -213,13 +221,7 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
                 const int fb = cb == 0 ? (NHB - 1) * HSLAB : cb - HSLAB;         // ... of slab sl - 1 = of slab sl + 3
                 // Loads are issued in the order ... D(s+2) R(s+3) | D(s+3) R(s+4) | ... (D: the HL loads of a hidden_t
                 // slab, after the barrier of slab s; R: the 8 W_lm loads of a line, at the end of slab s) and complete
-                // in that order.  Line sl is needed now: everything up to R(sl) has landed once at most the loads after
-                // it - D(sl) R(sl+1) D(sl+1) R(sl+2) D(sl+2) R(sl+3) - are outstanding.  The registers are operands
-                // of the wait, so nothing that reads them can be scheduled before it.
-                asm volatile("s_waitcnt vmcnt(%8)"
-                             : "+v"(ring[g][0]), "+v"(ring[g][1]), "+v"(ring[g][2]), "+v"(ring[g][3]), "+v"(ring[g][4]),
-                               "+v"(ring[g][5]), "+v"(ring[g][6]), "+v"(ring[g][7])
-                             : "n"(3 * (HL + 8)));
+                // in that order.
                 piece(g, 0, (2 * g) * MB, cb, cb, 1);
                 // Slab sl + 1 has landed once at most R(sl+2) D(sl+2) R(sl+3) are outstanding.  Every wave has finished
                 // slab sl - 1, so its buffer can take slab sl + 3 (wrapping into the next tile: hidden_t slabs are the
@@ -229,6 +231,16 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
                 if (a.M < 0)
 #endif
                 load_h(sl + 3 < NS ? sl + 3 : sl + 3 - NS, fb);
+                // Line sl + 1, whose registers the piece below rearranges, has landed once at most the loads after it -
+                // D(sl+1) R(sl+2) D(sl+2) R(sl+3) D(sl+3) - are outstanding.  The registers are operands of the wait, so
+                // nothing that reads them can be scheduled before it.
+                {
+                    u32x4(&rn)[8] = ring[(g + 1) & 3];
+                    asm volatile("s_waitcnt vmcnt(%8)"
+                                 : "+v"(rn[0]), "+v"(rn[1]), "+v"(rn[2]), "+v"(rn[3]), "+v"(rn[4]), "+v"(rn[5]), "+v"(rn[6]),
+                                   "+v"(rn[7])
+                                 : "n"(3 * HL + 16));
+                }
                 piece(g, 1, (2 * g + 1) * MB, cb, nb, 0);
                 refill(g, sl + 4);
                 cb = nb;

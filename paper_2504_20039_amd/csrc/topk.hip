@@ -98,8 +98,12 @@ __global__ __launch_bounds__(TK_WAVES * 64) void k_topk_tail(TopkArgs a)
             cn += __shfl_xor(cn, off);
         }
         if (lane == 0) {
-            // a token outside the vocabulary is in no top-k: rank V
-            const int32_t rank = j < K ? (a.thr_tok[row] >= 0 ? cn : a.V) : 0;
+            // a token outside the vocabulary is in no top-k: rank V.  The greedy token itself has rank 0 by
+            // definition (top_k = 1 is greedy verification): its threshold logit comes from a separate dot product
+            // whose rounding differs from the MFMA accumulation, so a runner-up within that rounding could otherwise
+            // be counted before it.
+            const int32_t tk = j < K ? a.thr_tok[row] : -1;
+            const int32_t rank = j < K ? (tk < 0 ? a.V : (tk == bi ? 0 : cn)) : 0;
             s_t[j] = bi;
             s_rej[j] = j < K && !(rank < a.top_k);
             a.t_star[row] = bi;
