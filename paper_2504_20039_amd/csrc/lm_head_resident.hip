@@ -49,6 +49,11 @@ __global__ __launch_bounds__(RS_WAVES * 64) void k_lm_head_resident(LmHeadArgs a
     // loads of 1 KB: 16 rows x 64 * UPV contiguous bytes) are requested in one burst, AHEAD visits before their use,
     // into one of NG register groups.
     constexpr int UPV = USES / RS_NBW;                       // 8 (bf16), 4 (FP8)
+    // PV: a visit covers a PAIR of blocks over half of the slab (32 rows x 64 * UPV / 2 bytes) instead of one block over
+    // all of it, and the two blocks share the hidden_t fragments of each k step: half the LDS reads, which is what
+    // bounds the kernel from 6 row blocks on and with FP8 weights (twice the MFMAs and fragment reads per streamed byte)
+    constexpr bool PV = FP8W || MB <= 7;
+    constexpr int LPB = UPV / 2, PPV = UPV / 2;              // PV: loads per block and pieces per visit
     constexpr int NG = FP8W && MB <= 5 ? 4 : 2, AHEAD = NG - 1;
     __shared__ __attribute__((aligned(1024))) char lds[2 * HSLAB];
     __shared__ Best fin[RS_WAVES][MB * 16];
@@ -147,7 +152,9 @@ __global__ __launch_bounds__(RS_WAVES * 64) void k_lm_head_resident(LmHeadArgs a
 #pragma unroll
         for (int v = 0; v < AHEAD; ++v)
 #pragma unroll
-            for (int p = 0; p < UPV; ++p) ring[v][p] = w_load(wcur, scur, v, p);
+            for (int p = 0; p < UPV; ++p)
+                ring[v][p] = PV ? w_load(wcur, scur, 2 * (v >> 1) + p / (UPV / 2), (v & 1) * (UPV / 2) + p % (UPV / 2))
+                                : w_load(wcur, scur, v, p);
     }
 
     for (int it = 0; it < total; ++it) {
@@ -188,33 +195,44 @@ __global__ __launch_bounds__(RS_WAVES * 64) void k_lm_head_resident(LmHeadArgs a
                 // a burst of UPV loads: the 16 rows of the block visited AHEAD visits from now, 64 * UPV contiguous
                 // bytes of each, into the registers of the visit that has just ended
                 {
-                    constexpr int dummy = 0;
-                    (void)dummy;
                     const int vv = v + AHEAD;
 #pragma unroll
-                    for (int p = 0; p < UPV; ++p)
-                        ring[vv % NG][p] = vv < RS_NBW ? w_load(wcur, scur, vv, p) : w_load(wnxt, snxt, vv - RS_NBW, p);
+                    for (int p = 0; p < UPV; ++p) {
+                        const int vs = vv < RS_NBW ? vv : vv - RS_NBW;           // visit within its slab
+                        // block and load index (2 * line + rows half) within the slab of load p of visit vs
+                        const int blk = PV ? 2 * (vs >> 1) + p / LPB : vs;
+                        const int j = PV ? (vs & 1) * LPB + p % LPB : p;
+                        ring[vv % NG][p] = vv < RS_NBW ? w_load(wcur, scur, blk, j) : w_load(wnxt, snxt, blk, j);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
+                // steps of the visit: a step is one 64-byte piece of the slab (k step(s) P) for the visit's block(s)
+                constexpr int NSTEP = PV ? PPV : UPV, NBS = PV ? 2 : 1;
+                // piece of the slab of step u (counted over the slab's 4 visits)
+                auto piece_of = [&](int u) { return PV ? ((u / NSTEP) & 1) * PPV + u % NSTEP : u % NSTEP; };
 #pragma unroll
-                for (int p = 0; p < UPV; ++p) {
-                    const int u = v * UPV + p, cur = HFB == 2 ? u & 1 : 0;
-                    if (HFB == 2 && u + 1 < USES) read_h((p + 1) % UPV, hf[cur ^ 1]);
-                    const u32x4 raw = half_of(ring[v % NG][p & ~1], ring[v % NG][p | 1], p & 1);
-                    if (FP8W) {
-                        const bf16x8 f0 = fp8x8_to_bf16x8(uint2{raw[0], raw[1]}), f1 = fp8x8_to_bf16x8(uint2{raw[2], raw[3]});
+                for (int q = 0; q < NSTEP; ++q) {
+                    const int u = v * NSTEP + q, cur = HFB == 2 ? u & 1 : 0;
+                    if (HFB == 2 && u + 1 < 4 * NSTEP) read_h(piece_of(u + 1), hf[cur ^ 1]);
 #pragma unroll
-                        for (int y = 0; y < MB; ++y) {
-                            acc[v][y] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0, hf[cur][0][y], acc[v][y], 0, 0, 0);
-                            acc[v][y] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1, hf[cur][NK - 1][y], acc[v][y], 0, 0, 0);
+                    for (int bb = 0; bb < NBS; ++bb) {
+                        const int base = PV ? bb * LPB + (q >> 1) * 2 : (q & ~1), blk = PV ? 2 * (v >> 1) + bb : v;
+                        const u32x4 raw = half_of(ring[v % NG][base], ring[v % NG][base + 1], q & 1);
+                        if (FP8W) {
+                            const bf16x8 f0 = fp8x8_to_bf16x8(uint2{raw[0], raw[1]}), f1 = fp8x8_to_bf16x8(uint2{raw[2], raw[3]});
+#pragma unroll
+                            for (int y = 0; y < MB; ++y) {
+                                acc[blk][y] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0, hf[cur][0][y], acc[blk][y], 0, 0, 0);
+                                acc[blk][y] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f1, hf[cur][NK - 1][y], acc[blk][y], 0, 0, 0);
+                            }
+                        } else {
+                            const bf16x8 f0 = __builtin_bit_cast(bf16x8, raw);
+#pragma unroll
+                            for (int y = 0; y < MB; ++y)
+                                acc[blk][y] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0, hf[cur][0][y], acc[blk][y], 0, 0, 0);
                         }
-                    } else {
-                        const bf16x8 f0 = __builtin_bit_cast(bf16x8, raw);
-#pragma unroll
-                        for (int y = 0; y < MB; ++y)
-                            acc[v][y] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f0, hf[cur][0][y], acc[v][y], 0, 0, 0);
                     }
-                    if (HFB == 1 && u + 1 < USES) read_h((p + 1) % UPV, hf[0]);
+                    if (HFB == 1 && u + 1 < 4 * NSTEP) read_h(piece_of(u + 1), hf[0]);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
