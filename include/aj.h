@@ -94,8 +94,9 @@ typedef struct {
     int32_t kernel;      /* AJ_KERNEL_* */
     int32_t w_dtype;     /* storage of W_lm: AJ_W_SAME (0) = `dtype`; AJ_W_FP8_E4M3 = OCP FP8 E4M3 bytes [V][d_t],
                             widened exactly to bf16 in registers (the 405B run of Section 4 serves the LM head in
-                            FP8); needs dtype = AJ_BF16, B*(K+1) <= 128 and d_t a multiple of 256 (AJ_EINVAL
-                            otherwise) and is not available to aj_verify_topk.  A per-tensor scale of the FP8 weights is the caller's
+                            FP8); needs dtype = AJ_BF16 and either B*(K+1) <= 128 with d_t a multiple of 256 or
+                            B*(K+1) <= 272 with d_t a multiple of 512 (AJ_EINVAL otherwise: beyond that the path is
+                            bound by the matrix pipe, not by the bytes of W_lm) and is not available to aj_verify_topk.  A per-tensor scale of the FP8 weights is the caller's
                             business: no step of the path depends on the scale of the logits except the
                             temperature of aj_verify_sampled, into which it can be folded. */
 } aj_config;

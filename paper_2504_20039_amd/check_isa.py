@@ -50,26 +50,29 @@ def check(hipcc, flags, verbose=False):
         subprocess.run([hipcc, *flags, "-S", "--cuda-device-only", "-o", asm, os.path.join(CSRC, "lm_head_wide.hip")],
                        check=True, capture_output=True)
         for name, lines in _kernels(open(asm).read()).items():
-            m = re.search(r"k_lm_head_wideILi(\d+)ELb(\d)ELb(\d)ELb(\d)E", name)
-            if not m or m.group(2) == "1":
+            m = re.search(r"k_lm_head_wideILi(\d+)ELb(\d)ELb(\d)ELb(\d)ELb(\d)E", name)
+            if not m or m.group(3) == "1":
                 continue
-            mb = int(m.group(1))
+            mb, fp8 = int(m.group(1)), m.group(2) == "1"
+            tag = f"lm_head_wide MB={mb}{' fp8' if fp8 else ''}"
             loop = _innermost_loop(lines)
             if loop is None:
                 problems.append(f"{name}: no inner loop found")
                 continue
             hl = (2 * mb + 3) // 4
-            own = {f"vmcnt({3 * hl + 16})", f"vmcnt({hl + 16})"}
+            # a trip of the loop: 4 lines of W_lm = 4 hidden_t slabs (8 with FP8 weights) of 2 pieces of 4 * MB MFMAs
+            own = {f"vmcnt({2 * hl + 8})", f"vmcnt({hl + 8})"} if fp8 else {f"vmcnt({3 * hl + 16})", f"vmcnt({hl + 16})"}
             for l in loop:
                 if "scratch_" in l or "v_accvgpr" in l:
-                    problems.append(f"lm_head_wide MB={mb}: '{l.strip()}' inside the slab loop")
+                    problems.append(f"{tag}: '{l.strip()}' inside the slab loop")
                     break
                 w = re.search(r"s_waitcnt\s+(vmcnt\(\d+\))", l)
                 if w and w.group(1) not in own:
-                    problems.append(f"lm_head_wide MB={mb}: compiler wait '{l.strip()}' inside the slab loop")
+                    problems.append(f"{tag}: compiler wait '{l.strip()}' inside the slab loop")
                     break
-            if sum("v_mfma" in l for l in loop) != 32 * mb:
-                problems.append(f"lm_head_wide MB={mb}: {sum('v_mfma' in l for l in loop)} MFMAs in the loop, expected {32 * mb}")
+            want = (64 if fp8 else 32) * mb
+            if sum("v_mfma" in l for l in loop) != want:
+                problems.append(f"{tag}: {sum('v_mfma' in l for l in loop)} MFMAs in the loop, expected {want}")
         # ---- lm_head_pair9.hip: nothing spilled and no accumulator moved inside the k loop (its ninth row block lives
         # in VGPRs next to hand-written MFMAs; the code around the loop may spill)
         asm = os.path.join(tmp, "pair9.s")

@@ -102,22 +102,28 @@ static int plan_handle(const aj_config &c, aj_handle *h)
         return AJ_EINVAL;
     }
     if (c.w_dtype == AJ_W_FP8_E4M3) {
-        // FP8 weights: the two W_lm-streaming kernels only (up to 128 verify rows), and no top-K baseline (its
-        // pre-pass reads W_lm rows)
+        // FP8 weights: the kernels that stream W_lm straight into registers (up to 272 verify rows; beyond that the path
+        // is bound by the matrix pipe and the bytes of W_lm cost no time), and no top-K baseline (its pre-pass reads
+        // W_lm rows)
         if (c.dtype != AJ_BF16 || (c.flags & (AJ_FLAG_TOPK | AJ_FLAG_FUSED_JUDGE))) return AJ_EINVAL;
         const bool s16 = (c.kernel == AJ_KERNEL_AUTO || c.kernel == AJ_KERNEL_STREAM) &&
                          lm_head_stream16_fp8w_supports(h->M, c.V, c.d_t);
         const bool res = (c.kernel == AJ_KERNEL_AUTO || c.kernel == AJ_KERNEL_RESIDENT) &&
                          lm_head_resident_supports(h->M, c.V, c.d_t, true);
-        if (h->M > 0 && !s16 && !res) return AJ_EINVAL;
+        const bool wide = (c.kernel == AJ_KERNEL_AUTO || c.kernel == AJ_KERNEL_WIDE) &&
+                          lm_head_wide_supports(h->M, c.V, c.d_t, true);
+        if (h->M > 0 && !s16 && !res && !wide) return AJ_EINVAL;
         h->fp8w = true;
         if (s16 || h->M == 0) {
             h->variant = AJ_KERNEL_STREAM;
             h->stream16 = true;
             h->nblocks = lm_head_stream16_blocks(c.V, h->num_cus);
-        } else {
+        } else if (res) {
             h->variant = AJ_KERNEL_RESIDENT;
             h->nblocks = lm_head_resident_blocks(c.V, h->num_cus);
+        } else {
+            h->variant = AJ_KERNEL_WIDE;
+            h->nblocks = lm_head_wide_blocks(c.V);
         }
     } else if (c.dtype == AJ_F32) {
         if (c.kernel != AJ_KERNEL_AUTO || (c.flags & AJ_FLAG_FUSED_JUDGE)) {
@@ -143,7 +149,7 @@ static int plan_handle(const aj_config &c, aj_handle *h)
                 v = AJ_KERNEL_STREAM;
             } else if (lm_head_resident_supports(h->M, c.V, c.d_t, false)) {
                 v = AJ_KERNEL_RESIDENT;     // up to 128 rows at any hidden size that is a multiple of 256
-            } else if (h->M <= 240 && lm_head_wide_supports(h->M, c.V, c.d_t)) {
+            } else if (h->M <= 240 && lm_head_wide_supports(h->M, c.V, c.d_t, false)) {
                 // 129..240 rows: W_lm straight into registers, 16-row blocks (0.39 ms against 0.46 of a padded 256-row
                 // tile at 144 rows of the 70B shape, 0.48 against 0.51 at 224; from 256 rows on the LDS-fed tiles are
                 // as fast or faster)
@@ -171,7 +177,7 @@ static int plan_handle(const aj_config &c, aj_handle *h)
         } else if (v == AJ_KERNEL_RESIDENT) {
             if (h->M > 0 && !lm_head_resident_supports(h->M, c.V, c.d_t, false)) return AJ_EINVAL;
         } else if (v == AJ_KERNEL_WIDE) {
-            if (h->M > 0 && !lm_head_wide_supports(h->M, c.V, c.d_t)) return AJ_EINVAL;
+            if (h->M > 0 && !lm_head_wide_supports(h->M, c.V, c.d_t, false)) return AJ_EINVAL;
         } else if (v == AJ_KERNEL_PAIR || v == AJ_KERNEL_PAIR9 ? (h->M > 0 && !lm_head_pair_supports(h->M, c.V, c.d_t))
                    : v != AJ_KERNEL_TILE && h->M > 0 && !lm_head_mfma_supports(v, h->M, c.V, c.d_t) &&
                          !(v == AJ_KERNEL_STREAM && lm_head_stream16_supports(h->M, c.V, c.d_t))) {
@@ -282,7 +288,7 @@ static hipError_t launch_lm_head(aj_handle *h, const void *hidden_t, const void 
     if (h->variant == AJ_KERNEL_TILE) return lm_head_tile_bf16(a, s);
     if (h->variant == AJ_KERNEL_RESIDENT)
         return h->fp8w ? lm_head_resident_fp8w(a, h->num_cus, s) : lm_head_resident_bf16(a, h->num_cus, s);
-    if (h->variant == AJ_KERNEL_WIDE) return lm_head_wide_bf16(a, h->num_cus, s);
+    if (h->variant == AJ_KERNEL_WIDE) return h->fp8w ? lm_head_wide_fp8w(a, h->num_cus, s) : lm_head_wide_bf16(a, h->num_cus, s);
     if (h->fp8w) return lm_head_stream16_fp8w(a, h->num_cus, s);
     if (h->stream16) return lm_head_stream16_bf16(a, h->num_cus, s);
     if (h->variant == AJ_KERNEL_PAIR) return lm_head_pair_bf16(a, h->num_cus, s);
@@ -553,7 +559,7 @@ extern "C" const char *aj_kernel_name(const aj_handle *h)
         case AJ_KERNEL_TALL: return "lm_head_tall_bf16";
         case AJ_KERNEL_PAIR: return "lm_head_pair_bf16";
         case AJ_KERNEL_PAIR9: return "lm_head_pair9_bf16";
-        case AJ_KERNEL_WIDE: return "lm_head_wide_bf16";
+        case AJ_KERNEL_WIDE: return h->fp8w ? "lm_head_wide_fp8w" : "lm_head_wide_bf16";
         case AJ_KERNEL_RESIDENT: return h->fp8w ? "lm_head_resident_fp8w" : "lm_head_resident_bf16";
         default: return "unknown";
     }

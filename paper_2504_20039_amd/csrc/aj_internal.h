@@ -121,9 +121,10 @@ hipError_t lm_head_resident_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s
 hipError_t lm_head_resident_fp8w(const LmHeadArgs &a, int num_cus, hipStream_t s);
 
 // 129..272 verify rows in one row tile: 256 vocabulary rows x 16-row blocks, W_lm global -> registers (d_t % 256 == 0)
-bool lm_head_wide_supports(int M, int V, int d);
+bool lm_head_wide_supports(int M, int V, int d, bool fp8w);
 int lm_head_wide_blocks(int V);
 hipError_t lm_head_wide_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s);
+hipError_t lm_head_wide_fp8w(const LmHeadArgs &a, int num_cus, hipStream_t s);
 
 // 256 x 256 tiles with paired 64-byte half loads (whole 128-byte lines per request pair); d_t % 256 == 0
 bool lm_head_pair_supports(int M, int V, int d);

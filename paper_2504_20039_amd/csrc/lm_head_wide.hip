@@ -33,9 +33,13 @@ constexpr int WD_KS = 64;                       // k elements per hidden_t slab:
 constexpr int WD_HROW = WD_KS * 2;              // bytes of a hidden_t row per slab
 constexpr int WD_MAXB = 17;
 
-template <int MB, bool DUMP, bool TOPK, bool SAMPLE>
+template <int MB, bool FP8W, bool DUMP, bool TOPK, bool SAMPLE>
 __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, int ntiles)
 {
+    // FP8 weights: a 128-byte line of a W_lm row holds 128 k elements = TWO hidden_t slabs; everything else (ring,
+    // loads, layout moves, slab pipeline) is the same, and a lane's 16 bytes of a line half - 16 k elements, its share of
+    // the slab's two pieces - are widened to bf16 (exactly) one piece ahead of their use
+    constexpr int SPG = FP8W ? 2 : 1;                           // hidden_t slabs per W_lm line
     constexpr int HSLAB = MB * 16 * WD_HROW;                    // bytes of a hidden_t slab in LDS
     constexpr int MBA = MB > 16 ? 16 : MB;                      // row blocks accumulated through the builtin
     constexpr int NHB = 4;                                      // hidden_t slab buffers
@@ -46,8 +50,9 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l16 = lane & 15, q4 = lane >> 4;
     const char *H = (const char *)a.H;
-    const uint32_t wrow = (uint32_t)a.d * 2u;
-    const int NS = a.d / WD_KS;                                 // slabs (= lines) per tile: a multiple of 4 (host: d % 256 == 0)
+    const uint32_t wrow = (uint32_t)a.d * (FP8W ? 1u : 2u);     // bytes of a W_lm row
+    const uint32_t hrow = (uint32_t)a.d * 2u;                   // bytes of a hidden_t row
+    const int NS = a.d / WD_KS;                                 // slabs per tile: a multiple of 4 * SPG (host)
 
     // ---- hidden_t slab loader: a load covers 8 LDS rows x 128 B (1 KB); load i of wave w covers row group 4i + w
     // (beyond the slab: its last group once more - same data to the same place); lane (row lane/8, chunk slot lane%8)
@@ -64,7 +69,7 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
         for (int i = 0; i < HL; ++i) {
             const int gg = min(i * WD_WAVES + wave + z, HG - 1);
             const int hr = 8 * gg + (lane >> 3);         // rows beyond M repeat the last one (their logits are never looked at)
-            lds_dma_16(hb, __umul24(min(hr, a.M - 1), wrow) + (uint32_t)(((lane & 7) ^ ((hr >> 1) & 7)) * 16),
+            lds_dma_16(hb, __umul24(min(hr, a.M - 1), hrow) + (uint32_t)(((lane & 7) ^ ((hr >> 1) & 7)) * 16),
                        lds_base + bufoff + gg * 1024);
         }
     };
@@ -104,38 +109,59 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
 
     f32x4 acc[4][MBA], accv[4];       // accv: row block 16, in VGPRs
     u32x4 ring[4][8];                 // 4 lines x (4 blocks x 2 halves of the block's rows)
+    bf16x8 wf[2][4];                  // FP8 weights: the widened W_lm fragments of this piece and of the next
+    auto widen = [&](const u32x4 &x, int half) { return fp8x8_to_bf16x8(uint2{x[2 * half], x[2 * half + 1]}); };
     constexpr int HW = MB >= 15 ? 4 : 8;   // hidden_t fragment window (registers are scarce at 15+ row blocks)
     static_assert(MB >= HW, "the window reaches into the next piece only");
     bf16x8 hf[HW];
     // fragment of row block y, piece p (0, 1) of a slab: lds + buffer offset + hs[p] + y * 16 rows; the row-block part
-    // travels in the instruction's offset field
+    // travels in the instruction's offset field.  k elements of lane group q4 in piece p: 32p + 8*q4 .. + 7 (bf16 weights),
+    // 16*q4 + 8p .. + 7 (FP8 weights: the two halves of the lane's 16 bytes) - chunk 4p + q4 or 2*q4 + p of the row's 8
     const int hsw = (l16 >> 1) & 7;
-    const int hs[2] = {l16 * WD_HROW + ((q4 ^ hsw) * 16), l16 * WD_HROW + (((4 + q4) ^ hsw) * 16)};
+    const int hc0 = FP8W ? 2 * q4 : q4, hc1 = FP8W ? 2 * q4 + 1 : 4 + q4;
+    const int hs[2] = {l16 * WD_HROW + ((hc0 ^ hsw) * 16), l16 * WD_HROW + ((hc1 ^ hsw) * 16)};
     auto read_h = [&](const char *base, int y) { return *(const bf16x8 *)(base + y * 16 * WD_HROW); };
 
-    // one piece (p = 0, 1) of a slab: 4 x MB MFMAs with half p of ring group g.  n0 = index of the piece's first row
+    // one piece (p = 0, 1) of a slab: 4 x MB MFMAs with half p of ring group g (FP8 weights: with piece p of half hh of
+    // the group, widened during the piece before).  n0 = index of the piece's first row
     // block in the fragment sequence (mod HW); after row block y the window slot is refilled with the fragment HW
     // positions on: this piece's (buffer cb), or the next piece's (piece np of buffer nb)
-    auto piece = [&](int g, int p, int n0, int cb, int nb, int np) {
+    auto piece = [&](int g, int hh, int p, int n0, int cb, int nb, int np) {
         // the buffer offsets stay opaque run-time values: folded into constants (they cycle with the 4 slabs of a trip)
         // the compiler keeps dozens of precomputed LDS addresses in registers
         asm volatile("" : "+s"(cb), "+s"(nb));
         const char *bc = lds + (cb + hs[p]), *bn = lds + (nb + hs[np]);
-        // In the second piece of a line the NEXT line's registers are brought to the MFMA layout, one block after
+        // In the last piece of a line the NEXT line's registers are brought to the MFMA layout, one block after
         // every FS row blocks, in the shadow of the MFMAs (with one wave per SIMD nothing else covers VALU work; as a
-        // block of 48 moves before the first piece it left the matrix pipe idle for a tenth of the slab)
+        // block of 48 moves before the first piece it left the matrix pipe idle for a tenth of the slab).  FP8 weights:
+        // one row block later the next piece's fragments of that block are widened.
         constexpr int FS = MB / 4;
         const int gn = (g + 1) & 3;
+        const bool last = hh == SPG - 1 && p == 1;
 #pragma unroll
         for (int y = 0; y < MB; ++y) {
             const int slot = (n0 + y) % HW;
-            if (p == 1 && y % FS == 0 && y / FS < 4) to_mfma_layout(ring[gn][2 * (y / FS)], ring[gn][2 * (y / FS) + 1]);
+            if (last && y % FS == 0 && y / FS < 4) to_mfma_layout(ring[gn][2 * (y / FS)], ring[gn][2 * (y / FS) + 1]);
+            if (FP8W && y % FS == 1 && y / FS < 4) {
+                const int bb = y / FS;
+                if (p == 0) wf[1][bb] = widen(ring[g][2 * bb + hh], 1);
+                else if (!last) wf[0][bb] = widen(ring[g][2 * bb + 1], 0);
+                else wf[0][bb] = widen(ring[gn][2 * bb], 0);
+            }
             // Every MFMA is written out with its accumulator's register file stated: row blocks 0..15 in AGPRs (all
             // 256 of them), row block 16 in VGPRs.  Left to choose, the compiler moves accumulators between the two
             // files inside this loop.
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
-                if (y < MBA) {
+                if (FP8W) {
+                    if (y < MBA) {
+                        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"
+                                     : "+a"(acc[b][y < MBA ? y : 0])
+                                     : "v"(wf[p][b]), "v"(hf[slot]));
+                    } else {
+                        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(accv[b]) : "v"(wf[p][b]), "v"(hf[slot]));
+                    }
+                } else if (y < MBA) {
                     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0"
                                  : "+a"(acc[b][y < MBA ? y : 0])
                                  : "v"(ring[g][2 * b + p]), "v"(hf[slot]));
@@ -151,7 +177,7 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
     // The (tile, slab) sequence of a workgroup is ONE pipeline: hidden_t slabs are the same for every tile (a single
     // row tile), so slab loads simply wrap around, and ring refills past a tile's last line fetch the first lines of
     // the workgroup's next tile.  After the last tile both run on into data nobody uses.
-    const int lines = NS;                            // 128-byte lines per W_lm row
+    const int lines = NS / SPG;                      // 128-byte lines per W_lm row
     int T = blockIdx.x;
     if (T >= ntiles) return;
     {
@@ -172,6 +198,10 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
                  : "memory");
 #pragma unroll
     for (int b = 0; b < 4; ++b) to_mfma_layout(ring[0][2 * b], ring[0][2 * b + 1]);
+    if (FP8W) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) wf[0][b] = widen(ring[0][2 * b], 0);
+    }
 #pragma unroll
     for (int y = 0; y < HW; ++y) hf[y] = read_h(lds + hs[0], y);
     int cb = 0;                                       // byte offset of the LDS buffer of the slab being computed
@@ -212,48 +242,59 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
         // knows about: otherwise its own count-down waits for those loads end up inside the loop below, where from
         // the second trip on they would wait for the kernel's hand-written loads.
         __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
-        // four slabs per trip: slab s + g uses ring group g; the fragment sequence advances by 2 * MB per slab
-        for (int s = 0; s < NS; s += 4) {
+        // four lines per trip: line s / SPG + g uses ring group g; the fragment sequence advances by 2 * MB per slab
+        for (int s = 0; s < NS; s += 4 * SPG) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int sl = s + g;
-                const int nb = cb + HSLAB >= NHB * HSLAB ? 0 : cb + HSLAB;     // buffer of slab sl + 1
-                const int fb = cb == 0 ? (NHB - 1) * HSLAB : cb - HSLAB;         // ... of slab sl - 1 = of slab sl + 3
-                // Loads are issued in the order ... D(s+2) R(s+3) | D(s+3) R(s+4) | ... (D: the HL loads of a hidden_t
-                // slab, after the barrier of slab s; R: the 8 W_lm loads of a line, at the end of slab s) and complete
-                // in that order.
-                piece(g, 0, (2 * g) * MB, cb, cb, 1);
-                // Slab sl + 1 has landed once at most R(sl+2) D(sl+2) R(sl+3) are outstanding.  Every wave has finished
-                // slab sl - 1, so its buffer can take slab sl + 3 (wrapping into the next tile: hidden_t slabs are the
-                // same for every tile).
-                asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(HL + 16) : "memory");
+#pragma unroll
+                for (int hh = 0; hh < SPG; ++hh) {
+                    const int sl = s + g * SPG + hh, pi = 2 * (g * SPG + hh);
+                    const int nb = cb + HSLAB >= NHB * HSLAB ? 0 : cb + HSLAB;     // buffer of slab sl + 1
+                    const int fb = cb == 0 ? (NHB - 1) * HSLAB : cb - HSLAB;         // ... of slab sl - 1 = of slab sl + 3
+                    // Loads are issued in the order ... D(s+2) R(s+3) | D(s+3) R(s+4) | ... (D: the HL loads of a hidden_t
+                    // slab, after the barrier of slab s; R: the 8 W_lm loads of a line, at the end of slab s - with FP8
+                    // weights at the end of every second slab) and complete in that order.
+                    piece(g, hh, 0, pi * MB, cb, cb, 1);
+                    // Slab sl + 1 has landed once at most R(sl+2) D(sl+2) R(sl+3) are outstanding (FP8 weights: D(sl+2) and
+                    // the one R issued at the end of slab sl - 2 or sl - 1).  Every wave has finished
+                    // slab sl - 1, so its buffer can take slab sl + 3 (wrapping into the next tile: hidden_t slabs are the
+                    // same for every tile).
+                    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(HL + (FP8W ? 8 : 16)) : "memory");
 #ifdef WD_ABLATE_NO_H
-                if (a.M < 0)
+                    if (a.M < 0)
 #endif
-                load_h(sl + 3 < NS ? sl + 3 : sl + 3 - NS, fb);
-                // Line sl + 1, whose registers the piece below rearranges, has landed once at most the loads after it -
-                // D(sl+1) R(sl+2) D(sl+2) R(sl+3) D(sl+3) - are outstanding.  The registers are operands of the wait, so
-                // nothing that reads them can be scheduled before it.
-                {
-                    u32x4(&rn)[8] = ring[(g + 1) & 3];
-                    asm volatile("s_waitcnt vmcnt(%8)"
-                                 : "+v"(rn[0]), "+v"(rn[1]), "+v"(rn[2]), "+v"(rn[3]), "+v"(rn[4]), "+v"(rn[5]), "+v"(rn[6]),
-                                   "+v"(rn[7])
-                                 : "n"(3 * HL + 16));
+                    load_h(sl + 3 < NS ? sl + 3 : sl + 3 - NS, fb);
+                    // The next line, whose registers the piece below rearranges, has landed once at most the loads after it -
+                    // D(sl+1) R(sl+2) D(sl+2) R(sl+3) D(sl+3) - are outstanding (FP8 weights: it was issued six slabs
+                    // ago, before everything the wait above let through; D(sl+3) has been issued since).  The registers
+                    // are operands of the wait, so nothing that reads them can be scheduled before it.
+                    if (hh == SPG - 1) {
+                        u32x4(&rn)[8] = ring[(g + 1) & 3];
+                        asm volatile("s_waitcnt vmcnt(%8)"
+                                     : "+v"(rn[0]), "+v"(rn[1]), "+v"(rn[2]), "+v"(rn[3]), "+v"(rn[4]), "+v"(rn[5]), "+v"(rn[6]),
+                                       "+v"(rn[7])
+                                     : "n"(FP8W ? 2 * HL + 8 : 3 * HL + 16));
+                    }
+                    piece(g, hh, 1, (pi + 1) * MB, cb, nb, 0);
+                    if (hh == SPG - 1) refill(g, s / SPG + g + 4);
+                    cb = nb;
                 }
-                piece(g, 1, (2 * g + 1) * MB, cb, nb, 0);
-                refill(g, sl + 4);
-                cb = nb;
             }
         }
 
         // the hand-written MFMAs are invisible to the compiler's hazard handling: let the last of them retire
         // before their accumulators are read
         asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+        // (the lane's coordinates are derived again from an opaque copy of its index: values computed from them once, before
+        // the tile loop, would have to live - in scratch memory - across the slab loop, and their reloads bring the
+        // compiler's own waits for them into it)
+        int lane_e = lane;
+        asm volatile("" : "+v"(lane_e));
+        const int le16 = lane_e & 15, qe4 = lane_e >> 4;
         // ---- lane (l16, q4) holds verify row 16y + l16 against vocabulary rows v0 + 16b + 4*q4 + r, ascending in (b, r)
 #pragma unroll
         for (int y = 0; y < MB; ++y) {
-            const int row = y * 16 + l16, rowc = min(row, a.M - 1);
+            const int row = y * 16 + le16, rowc = min(row, a.M - 1);
             float th = INFINITY;
             int32_t tk = -1;
             if (TOPK) {
@@ -272,7 +313,7 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
             for (int b = 0; b < 4; ++b)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int v = v0 + b * 16 + q4 * 4 + r;
+                    const int v = v0 + b * 16 + qe4 * 4 + r;
                     float val = y < MBA ? acc[b][y < MBA ? y : 0][r] : accv[b][r];
                     if (v < a.V) {
                         if (DUMP && row < a.M) a.dump[(size_t)row * a.V + v] = val;
@@ -294,10 +335,12 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
                 }
                 if (TOPK) cn += __shfl_xor(cn, off);
             }
-            if (q4 == 0) {
+            if (qe4 == 0) {
                 red[wave][row] = Best{bv, bi};
                 if (TOPK) redc[wave][row] = cn;
             }
+            // one row block's accumulators at a time: read all at once they need more registers than there are
+            __builtin_amdgcn_sched_barrier(0);
         }
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         for (int row = threadIdx.x; row < MB * 16 && row < a.M; row += WD_WAVES * 64) {
@@ -318,45 +361,54 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
     }
 }
 
-template <int MB>
+template <int MB, bool FP8W>
 hipError_t launch_wide(const LmHeadArgs &a, int num_cus, hipStream_t s)
 {
     const int ntiles = (a.V + WD_N - 1) / WD_N;
     const int grid = ntiles < num_cus ? ntiles : num_cus;
     const dim3 g(grid), b(WD_WAVES * 64);
-    if (a.dump) hipLaunchKernelGGL((k_lm_head_wide<MB, true, false, false>), g, b, 0, s, a, ntiles);
-    else if (a.thr) hipLaunchKernelGGL((k_lm_head_wide<MB, false, true, false>), g, b, 0, s, a, ntiles);
-    else if (a.key) hipLaunchKernelGGL((k_lm_head_wide<MB, false, false, true>), g, b, 0, s, a, ntiles);
-    else hipLaunchKernelGGL((k_lm_head_wide<MB, false, false, false>), g, b, 0, s, a, ntiles);
+    if (a.dump) hipLaunchKernelGGL((k_lm_head_wide<MB, FP8W, true, false, false>), g, b, 0, s, a, ntiles);
+    else if (a.thr) {
+        if (FP8W) return hipErrorInvalidValue;       // no top-K baseline on FP8 weights (refused at create time)
+        hipLaunchKernelGGL((k_lm_head_wide<MB, false, false, true, false>), g, b, 0, s, a, ntiles);
+    } else if (a.key) hipLaunchKernelGGL((k_lm_head_wide<MB, FP8W, false, false, true>), g, b, 0, s, a, ntiles);
+    else hipLaunchKernelGGL((k_lm_head_wide<MB, FP8W, false, false, false>), g, b, 0, s, a, ntiles);
     return hipGetLastError();
+}
+
+template <bool FP8W>
+hipError_t dispatch_wide(const LmHeadArgs &a, int num_cus, hipStream_t s)
+{
+    if (a.M <= 0) return hipSuccess;
+    switch ((a.M + 15) / 16) {
+        case 9: return launch_wide<9, FP8W>(a, num_cus, s);
+        case 10: return launch_wide<10, FP8W>(a, num_cus, s);
+        case 11: return launch_wide<11, FP8W>(a, num_cus, s);
+        case 12: return launch_wide<12, FP8W>(a, num_cus, s);
+        case 13: return launch_wide<13, FP8W>(a, num_cus, s);
+        case 14: return launch_wide<14, FP8W>(a, num_cus, s);
+        case 15: return launch_wide<15, FP8W>(a, num_cus, s);
+        case 16: return launch_wide<16, FP8W>(a, num_cus, s);
+        case 17: return launch_wide<17, FP8W>(a, num_cus, s);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace
 
-bool lm_head_wide_supports(int M, int V, int d)
+bool lm_head_wide_supports(int M, int V, int d, bool fp8w)
 {
-    if (M <= 128 || M > WD_MAXB * 16 || V <= 0 || d < 256 || d % 256 != 0) return false;
-    if ((uint64_t)V * d * 2 >= (1ull << 32) || (uint64_t)M * d * 2 >= (1ull << 32)) return false;
+    // a trip of the slab loop covers 4 lines of a W_lm row: 256 k elements, 512 with FP8 weights
+    const int trip = fp8w ? 512 : 256, wb = fp8w ? 1 : 2;
+    if (M <= 128 || M > WD_MAXB * 16 || V <= 0 || d < trip || d % trip != 0) return false;
+    if ((uint64_t)V * d * wb >= (1ull << 32) || (uint64_t)M * d * 2 >= (1ull << 32)) return false;
     return V < (1 << 24) && d * 2 < (1 << 24);
 }
 
 int lm_head_wide_blocks(int V) { return (V + WD_N - 1) / WD_N; }
 
-hipError_t lm_head_wide_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s)
-{
-    if (a.M <= 0) return hipSuccess;
-    switch ((a.M + 15) / 16) {
-        case 9: return launch_wide<9>(a, num_cus, s);
-        case 10: return launch_wide<10>(a, num_cus, s);
-        case 11: return launch_wide<11>(a, num_cus, s);
-        case 12: return launch_wide<12>(a, num_cus, s);
-        case 13: return launch_wide<13>(a, num_cus, s);
-        case 14: return launch_wide<14>(a, num_cus, s);
-        case 15: return launch_wide<15>(a, num_cus, s);
-        case 16: return launch_wide<16>(a, num_cus, s);
-        case 17: return launch_wide<17>(a, num_cus, s);
-        default: return hipErrorInvalidValue;
-    }
-}
+hipError_t lm_head_wide_bf16(const LmHeadArgs &a, int num_cus, hipStream_t s) { return dispatch_wide<false>(a, num_cus, s); }
+
+hipError_t lm_head_wide_fp8w(const LmHeadArgs &a, int num_cus, hipStream_t s) { return dispatch_wide<true>(a, num_cus, s); }
 
 }  // namespace aj

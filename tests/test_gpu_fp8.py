@@ -27,7 +27,8 @@ def fp8_case(w, seed, tau=None, repeat=1, sampled=None):
         def scores_row(r):
             return oracle.logits_row(x.ht[r], x.W) * sampled[0] + np.array([oracle.gumbel(int(keys[r]), v) for v in range(w.V)])
     rep = compare(x, draft, tau, greedy, gpu, scores_row=scores_row)
-    assert gpu["kernel"] == ("lm_head_stream16_fp8w" if w.M <= 32 and w.d_t == 4096 else "lm_head_resident_fp8w")
+    assert gpu["kernel"] == ("lm_head_stream16_fp8w" if w.M <= 32 and w.d_t == 4096 else
+                             "lm_head_resident_fp8w" if w.M <= 128 else "lm_head_wide_fp8w")
     return rep, x, w8, gpu
 
 
@@ -40,6 +41,10 @@ def fp8_case(w, seed, tau=None, repeat=1, sampled=None):
     dict(B=1, K=64, V=140000, d_t=1024),   # 65 rows; more vocabulary than one pass holds
     dict(B=4, K=31, V=3000, d_t=512),      # 128 rows: all eight row blocks
     dict(B=2, K=15, V=1000, d_t=2048),     # 32 rows at a hidden size the 16-row-tile kernel does not take in FP8
+    dict(B=8, K=32, V=3000, d_t=1024),     # 264 rows: the wide kernel, 17 row blocks (the last one in VGPRs), ragged last tile
+    dict(B=3, K=42, V=70001, d_t=512),     # 129 rows: 9 row blocks, one trip of the slab loop, more tiles than workgroups
+    dict(B=4, K=59, V=1000, d_t=1536),     # 240 rows: 15 row blocks (the short fragment window)
+    dict(B=4, K=51, V=2000, d_t=512),      # 208 rows: 13 row blocks
 ])
 def test_fp8_weights(shape):
     w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="fp8", p_match=0.6, **shape)
@@ -58,7 +63,8 @@ def test_fp8_weights(shape):
     assert np.abs(logits.cpu().numpy() - ref).max() <= 1e-4 * np.abs(ref).max()
 
 
-@pytest.mark.parametrize("B,K,d_t", [(2, 15, 4096), (4, 31, 256)])      # the 16-row-tile kernel; the accumulator-resident one
+# the 16-row-tile kernel; the accumulator-resident one; the wide one
+@pytest.mark.parametrize("B,K,d_t", [(2, 15, 4096), (4, 31, 256), (8, 32, 512), (3, 47, 1024)])
 def test_every_fp8_code_is_widened_exactly(B, K, d_t):
     """One-hot hidden rows turn the logit dump into a read-out of the weights as the kernel sees them: every finite
     E4M3 code (subnormals, both zeros, +-448) must come out as the format defines it, bit for bit."""
@@ -92,10 +98,17 @@ def test_fp8_sampling_and_full_size():
     fp8_case(w, wl.DEFAULT_SEED, sampled=(scale, keys))
 
 
+def test_fp8_sampling_wide():
+    w = wl.scaled(wl.WORKLOADS["8b_b1_k16"], name="fp8", p_match=0.6, B=8, K=32, V=3000, d_t=1024)
+    keys = np.random.default_rng(5).integers(0, 2**63, size=(w.B, w.K + 1), dtype=np.uint64)
+    _, scale = wl.w_lm_fp8(w, 13)
+    fp8_case(w, 13, sampled=(scale, keys))
+
+
 def test_fp8_refusals():
     import paper_2504_20039_amd as aj
     ok = dict(B=1, K=16, d_t=4096, d_d=64, V=1000)
-    for bad in (dict(d_t=4096 + 64), dict(B=8), dict(dtype=aj.AJ_F32), dict(flags=aj.AJ_FLAG_TOPK), dict(kernel=aj.AJ_KERNEL_PAIR),
+    for bad in (dict(d_t=4096 + 64), dict(B=17), dict(B=8, d_t=768), dict(dtype=aj.AJ_F32), dict(flags=aj.AJ_FLAG_TOPK), dict(kernel=aj.AJ_KERNEL_PAIR),
                 dict(w_dtype=7)):
         a = dict(ok, dtype=aj.AJ_BF16, flags=0, kernel=0, w_dtype=aj.AJ_W_FP8_E4M3)
         a.update(bad)
