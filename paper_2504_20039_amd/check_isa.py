@@ -34,24 +34,33 @@ def _kernels(asm_text):
 
 
 def _innermost_loop(lines):
-    """Lines of the first innermost loop: from its header comment to the first branch after it."""
-    start = next((i for i, l in enumerate(lines) if "Inner Loop Header" in l), None)
-    if start is None:
-        return None
-    end = next((i for i in range(start + 1, len(lines)) if "s_cbranch" in lines[i]), len(lines))
-    return lines[start:end]
+    """Lines of the innermost loop that holds MFMAs: from its header label to the last branch back to that label
+    (the loop may hold forward branches of its own)."""
+    best = None
+    for i, l in enumerate(lines):
+        m = re.match(r"^(\.LBB\d+_\d+):", l)
+        if not m:
+            continue
+        back = re.compile(r"s_c?branch\w*\s+" + re.escape(m.group(1)) + r"\b")
+        ends = [j for j in range(i + 1, len(lines)) if back.search(lines[j])]
+        if not ends:
+            continue
+        body = lines[i:ends[-1] + 1]
+        if any("v_mfma" in x for x in body) and (best is None or len(body) < len(best)):
+            best = body
+    return best
 
 
 def check(hipcc, flags, verbose=False):
     problems = []
     with tempfile.TemporaryDirectory() as tmp:
-        # ---- lm_head_wide.hip: the greedy, top-K and sampling instantiations (the logit dump is a debug path)
+        # ---- lm_head_wide.hip: every instantiation
         asm = os.path.join(tmp, "wide.s")
         subprocess.run([hipcc, *flags, "-S", "--cuda-device-only", "-o", asm, os.path.join(CSRC, "lm_head_wide.hip")],
                        check=True, capture_output=True)
         for name, lines in _kernels(open(asm).read()).items():
             m = re.search(r"k_lm_head_wideILi(\d+)ELb(\d)ELb(\d)ELb(\d)ELb(\d)E", name)
-            if not m or m.group(3) == "1":
+            if not m:
                 continue
             mb, fp8 = int(m.group(1)), m.group(2) == "1"
             tag = f"lm_head_wide MB={mb}{' fp8' if fp8 else ''}"
@@ -61,13 +70,14 @@ def check(hipcc, flags, verbose=False):
                 continue
             hl = (2 * mb + 3) // 4
             # a trip of the loop: 4 lines of W_lm = 4 hidden_t slabs (8 with FP8 weights) of 2 pieces of 4 * MB MFMAs
-            own = {f"vmcnt({2 * hl + 8})", f"vmcnt({hl + 8})"} if fp8 else {f"vmcnt({3 * hl + 16})", f"vmcnt({hl + 16})"}
+            own = {f"vmcnt({hl + 8})"} if fp8 else {f"vmcnt({2 * hl + 16})", f"vmcnt({hl + 16})"}
             for l in loop:
                 if "scratch_" in l or "v_accvgpr" in l:
                     problems.append(f"{tag}: '{l.strip()}' inside the slab loop")
                     break
                 w = re.search(r"s_waitcnt\s+(vmcnt\(\d+\))", l)
-                if w and w.group(1) not in own:
+                # (a wait of the compiler's own costs time, not correctness: the logit dump, a debug path, may have one)
+                if w and w.group(1) not in own and m.group(3) != "1":
                     problems.append(f"{tag}: compiler wait '{l.strip()}' inside the slab loop")
                     break
             want = (64 if fp8 else 32) * mb

@@ -7,8 +7,10 @@
 //   * W_lm rows are private to a wave, so they never touch LDS: non-temporal buffer loads of whole 128-byte lines
 //     (8 rows x 128 B per instruction) straight into registers, brought to the MFMA layout by one DPP rotation per
 //     register, in place - the load path of lm_head_resident.hip.  A ring of 4 groups of 8 loads (64 rows x one line); a group
-//     is refilled, in one burst, right after its second half has been used: 24 KB per wave in flight, three lines
-//     (3.3 us of MFMA work) ahead.  The loads are hand-written with the kernel's own s_waitcnt accounting.
+//     is refilled as its registers fall free, three lines (3.3 us of MFMA work) ahead, ONE load after a row block's
+//     MFMAs at a time.  The loads are hand-written with the kernel's own s_waitcnt accounting, and all of a load's address but
+//     one lane offset travels in scalar registers: with one wave per SIMD, whatever the wave does that is not an MFMA
+//     leaves the matrix pipe idle.
 //   * hidden_t is shared by the 4 waves: slabs of 64 k elements (16*MB rows x one 128-byte line) staged in LDS, four
 //     buffers (three slabs ahead), by asynchronous direct-to-LDS loads; one workgroup barrier per slab.  A slab is 2 pieces of 32 k; a
 //     piece is 4 x MB MFMAs ordered row block by row block.  The hidden_t fragments are a rolling window of 8: the
@@ -49,6 +51,13 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int l16 = lane & 15, q4 = lane >> 4;
+    // The lane index once more, for the rarely taken paths (rows beyond M or V, the epilogue): derived on the spot from an
+    // opaque zero, so that neither it nor anything computed from it occupies a register across the slab loop
+    auto lane_now = [] {
+        int zz = 0;
+        asm volatile("" : "+v"(zz));
+        return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, (uint32_t)zz));
+    };
     const char *H = (const char *)a.H;
     const uint32_t wrow = (uint32_t)a.d * (FP8W ? 1u : 2u);     // bytes of a W_lm row
     const uint32_t hrow = (uint32_t)a.d * 2u;                   // bytes of a hidden_t row
@@ -59,19 +68,31 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
     // fetches global chunk slot ^ ((row / 2) % 8), so that the fragment reads are conflict free.  The group index
     // depends on an opaque scalar, so that each lane offset is computed here (a few VALU operations) instead of living in a
     // register, and in scratch memory, across the kernel.
+    // A group that lies inside the M rows (all but the last one or two of a slab) is loaded with ONE lane offset, that of
+    // the wave's first group (the swizzle term does not depend on i: rows 32 apart), the group's distance travelling in the
+    // scalar base address - scalar instructions only.  One wave per SIMD: nothing covers vector work that is not an MFMA.
     constexpr int HG = 2 * MB, HL = (HG + WD_WAVES - 1) / WD_WAVES;     // row groups per slab, loads per wave
     const uint32_t lds_base = lds_offset_of(lds);
-    auto load_h = [&](int slab, int bufoff) {
+    const uint32_t hoff0 = __umul24(8 * wave + (lane >> 3), hrow) + (uint32_t)(((lane & 7) ^ ((4 * wave + (lane >> 4)) & 7)) * 16);
+    auto load_h1 = [&](int slab, int bufoff, int i) {        // load i (0 .. HL - 1) of a slab
         const char *hb = H + (size_t)slab * WD_HROW;
-        int z = 0;
-        asm volatile("" : "+s"(z));                      // an opaque zero
-#pragma unroll
-        for (int i = 0; i < HL; ++i) {
-            const int gg = min(i * WD_WAVES + wave + z, HG - 1);
-            const int hr = 8 * gg + (lane >> 3);         // rows beyond M repeat the last one (their logits are never looked at)
-            lds_dma_16(hb, __umul24(min(hr, a.M - 1), hrow) + (uint32_t)(((lane & 7) ^ ((hr >> 1) & 7)) * 16),
+        // M > 16 * (MB - 1): groups 0 .. HG - 3 lie inside the M rows whatever M is
+        constexpr int IF = (HG - 6) / WD_WAVES + 1;      // loads i < IF touch those groups only
+        const int gq = i * WD_WAVES + wave;
+        if (i < IF) {
+            lds_dma_16(hb + (size_t)i * (32 * hrow), hoff0, lds_base + bufoff + gq * 1024);
+        } else {
+            int z = 0;
+            asm volatile("" : "+s"(z));                  // an opaque zero
+            const int gg = min(gq + z, HG - 1), ln = lane_now();
+            const int hr = 8 * gg + (ln >> 3);           // rows beyond M repeat the last one (their logits are never looked at)
+            lds_dma_16(hb, __umul24(min(hr, a.M - 1), hrow) + (uint32_t)(((ln & 7) ^ ((hr >> 1) & 7)) * 16),
                        lds_base + bufoff + gg * 1024);
         }
+    };
+    auto load_h = [&](int slab, int bufoff) {
+#pragma unroll
+        for (int i = 0; i < HL; ++i) load_h1(slab, bufoff, i);
     };
 
     // ---- W_lm loads (see lm_head_resident.hip): load 2*blk + h of a line covers rows 8h .. 8h+7 of block blk
@@ -80,20 +101,21 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
     // than needed and let only one line of W_lm be in flight.
     const uint64_t wbase = (uint64_t)a.W;
     const u32x4 wres = {(uint32_t)wbase, (uint32_t)(wbase >> 32), (uint32_t)a.V * wrow, 0x00020000u};   // raw buffer
-    const int r8 = l16 & 7;
-    const uint32_t cbyte = (uint32_t)(q4 + 4 * (l16 >> 3)) * 16u;
-    auto w_load = [&](u32x4 &dst, int v0, int line, int j) {      // line: index of the 128-byte line in the row
-        int r0 = v0 + (j >> 1) * 16 + (j & 1) * 8;      // opaque scalar: see load_h
-        asm volatile("" : "+s"(r0));
-#ifdef WD_ABLATE_W_FROM_L2
-        const int row = min(r0 + r8, a.V - 1) & 255;     // every workgroup reads the same 256 rows: W_lm from L2
-#else
-        const int row = min(r0 + r8, a.V - 1);
-#endif
+    // lane (l16, q4): row l16 % 8 of a group of 8, bytes (q4 + 4 * (l16 / 8)) * 16 .. + 15 of the line
+    const uint32_t woff0 = __umul24(l16 & 7, wrow) + (uint32_t)(q4 + 4 * (l16 >> 3)) * 16u;
+    // vb: first of the wave's 64 rows; load j of a burst covers rows vb + 8j .. + 7 of line `line` (the index of the 128-byte
+    // line in the row).  One lane offset serves every load, the rest of the address travels in the scalar offset - scalar
+    // instructions only.  A wave whose 64 rows would reach beyond the vocabulary (in the last tile) starts at V - 64
+    // instead, so that every row it reads exists; the epilogue drops the logits of the rows below its own range.
+    auto w_load1 = [&](u32x4 &dst, int vb, int line, int j) {
         asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen nt"
                      : "=v"(dst)
-                     : "v"(__umul24(row, wrow) + cbyte), "s"(wres), "s"(line * 128)
+                     : "v"(woff0), "s"(wres), "s"((uint32_t)(vb + 8 * j) * wrow + (uint32_t)line * 128u)
                      : "memory");
+    };
+    auto w_burst = [&](u32x4(&dst)[8], int vb, int line) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) w_load1(dst[j], vb, line, j);
     };
     // The two loads of a block's line (x: rows 0..7, y: rows 8..15; lanes l16 < 8 hold the first 64 bytes, the others
     // the second) become, in place, the block's two k steps in MFMA layout (lane l16 <-> row l16): x keeps its lower
@@ -126,7 +148,10 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
     // the group, widened during the piece before).  n0 = index of the piece's first row
     // block in the fragment sequence (mod HW); after row block y the window slot is refilled with the fragment HW
     // positions on: this piece's (buffer cb), or the next piece's (piece np of buffer nb)
-    auto piece = [&](int g, int hh, int p, int n0, int cb, int nb, int np) {
+    // `after(y)` runs after the MFMAs of row block y: the loads of the step, one at a time - a burst of them fills the
+    // address queue of the vector-memory path and the wave, the only one of its SIMD, stands at the load instead of
+    // issuing MFMAs
+    auto piece = [&](int g, int hh, int p, int n0, int cb, int nb, int np, auto after) {
         // the buffer offsets stay opaque run-time values: folded into constants (they cycle with the 4 slabs of a trip)
         // the compiler keeps dozens of precomputed LDS addresses in registers
         asm volatile("" : "+s"(cb), "+s"(nb));
@@ -170,6 +195,7 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
                 }
             }
             hf[slot] = y + HW < MB ? read_h(bc, y + HW) : read_h(bn, y + HW - MB);
+            after(y);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -181,11 +207,14 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
     int T = blockIdx.x;
     if (T >= ntiles) return;
     {
-        const int v0 = T * WD_N + wave * 64;
+        // lines 0..2 whole and the even registers of line 3: its odd ones are loaded in the first piece of slab 0, like those of
+        // every later line.  (No hand-written load may go into a register that is overwritten before it is read: the
+        // compiler gives such an output a register it also uses for other values, and the data arrives later.)
+        const int vb = min(T * WD_N + wave * 64, a.V - 64);
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
+        for (int g = 0; g < 3; ++g) w_burst(ring[g], vb, g);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) w_load(ring[g][j], v0, g, j);
+        for (int j = 0; j < 8; j += 2) w_load1(ring[3][j], vb, 3, j);
     }
     load_h(0, 0);
     load_h(1, HSLAB);
@@ -207,7 +236,8 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
     int cb = 0;                                       // byte offset of the LDS buffer of the slab being computed
 
     for (; T < ntiles; T += gridDim.x) {
-        const int v0 = T * WD_N + wave * 64, v0n = v0 + (int)gridDim.x * WD_N;
+        // v0: first vocabulary row of the wave's own range; vb, vbn: first row it reads in this tile and in its next one
+        const int v0 = T * WD_N + wave * 64, vb = min(v0, a.V - 64), vbn = min(v0 + (int)gridDim.x * WD_N, a.V - 64);
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
 #pragma unroll
@@ -223,60 +253,53 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
             asm volatile("" : "+v"(accv[b]));
         }
         asm volatile("s_nop 7" ::: "memory");
-        auto refill = [&](int g, int line) {         // a burst of 8 loads: 64 rows x one line
-#ifdef WD_ABLATE_NO_W
-            return;
-#endif
+        // load j of the refill of ring group g with line `line` (past the tile's last line: of the workgroup's next tile)
+        auto refill1 = [&](int g, int line, int j) {
             const bool wrap = line >= lines;
-            int vv = wrap ? v0n : v0;
-            const int ll = wrap ? line - lines : line;
-            // opaque, so that the 8 lane offsets are computed here (a few VALU operations beside hundreds of MFMA
-            // cycles) instead of living in registers - and in scratch memory - across the loop
-            asm volatile("" : "+s"(vv));
-#pragma unroll
-            for (int j = 0; j < 8; ++j) w_load(ring[g][j], vv, ll, j);
-            __builtin_amdgcn_sched_barrier(0);
+            w_load1(ring[g][j], wrap ? vbn : vb, wrap ? line - lines : line, j);
         };
 
         // Whatever the compiler itself has loaded up to here (spilled values) has landed after this wait, which it
         // knows about: otherwise its own count-down waits for those loads end up inside the loop below, where from
         // the second trip on they would wait for the kernel's hand-written loads.
         __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
-        // four lines per trip: line s / SPG + g uses ring group g; the fragment sequence advances by 2 * MB per slab
+        // Four lines per trip: line L = s / SPG + g uses ring group g; the fragment sequence advances by 2 * MB per slab.
+        // Loads of slab sl, one after a row block's MFMAs each, in this order:
+        //   first piece:  Ro - in a line's first slab, the 4 loads of the odd registers of the group before (its line L + 3)
+        //   second piece: D  - the HL loads of hidden_t slab sl + 3 (its buffer is free after the barrier between the pieces)
+        //                 Re - in a line's last slab, the 4 loads of the even registers of this group (line L + 4): a group's
+        //                      even registers were last read in the first piece of its last slab, the odd ones in the second
+        // and they complete in that order.
         for (int s = 0; s < NS; s += 4 * SPG) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
 #pragma unroll
                 for (int hh = 0; hh < SPG; ++hh) {
-                    const int sl = s + g * SPG + hh, pi = 2 * (g * SPG + hh);
+                    const int sl = s + g * SPG + hh, pi = 2 * (g * SPG + hh), L = s / SPG + g;
                     const int nb = cb + HSLAB >= NHB * HSLAB ? 0 : cb + HSLAB;     // buffer of slab sl + 1
                     const int fb = cb == 0 ? (NHB - 1) * HSLAB : cb - HSLAB;         // ... of slab sl - 1 = of slab sl + 3
-                    // Loads are issued in the order ... D(s+2) R(s+3) | D(s+3) R(s+4) | ... (D: the HL loads of a hidden_t
-                    // slab, after the barrier of slab s; R: the 8 W_lm loads of a line, at the end of slab s - with FP8
-                    // weights at the end of every second slab) and complete in that order.
-                    piece(g, hh, 0, pi * MB, cb, cb, 1);
-                    // Slab sl + 1 has landed once at most R(sl+2) D(sl+2) R(sl+3) are outstanding (FP8 weights: D(sl+2) and
-                    // the one R issued at the end of slab sl - 2 or sl - 1).  Every wave has finished
-                    // slab sl - 1, so its buffer can take slab sl + 3 (wrapping into the next tile: hidden_t slabs are the
-                    // same for every tile).
-                    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(HL + (FP8W ? 8 : 16)) : "memory");
-#ifdef WD_ABLATE_NO_H
-                    if (a.M < 0)
-#endif
-                    load_h(sl + 3 < NS ? sl + 3 : sl + 3 - NS, fb);
-                    // The next line, whose registers the piece below rearranges, has landed once at most the loads after it -
-                    // D(sl+1) R(sl+2) D(sl+2) R(sl+3) D(sl+3) - are outstanding (FP8 weights: it was issued six slabs
-                    // ago, before everything the wait above let through; D(sl+3) has been issued since).  The registers
-                    // are operands of the wait, so nothing that reads them can be scheduled before it.
+                    piece(g, hh, 0, pi * MB, cb, cb, 1, [&](int y) {
+                        if (hh == 0 && y < 4) refill1((g + 3) & 3, L + 3, 2 * y + 1);
+                    });
+                    // Slab sl + 1 has landed once at most what was issued after its loads is outstanding: Re Ro D(sl+2) Re
+                    // Ro (FP8 weights: D(sl+2) and one Re Ro pair).  Every wave has finished slab sl - 1, so its buffer
+                    // can take slab sl + 3 (wrapping into the next tile: hidden_t slabs are the same for every tile).
+                    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(HL + (FP8W ? 8 : 16)) : "memory");
+                    // The next line, whose registers the piece below rearranges, has landed once at most the loads after
+                    // its last one - D(sl+1) Re Ro D(sl+2) Re Ro - are outstanding (FP8 weights: it was issued five
+                    // slabs ago, before everything the wait above let through).  The registers are operands of
+                    // the wait, so nothing that reads them can be scheduled before it.
                     if (hh == SPG - 1) {
                         u32x4(&rn)[8] = ring[(g + 1) & 3];
                         asm volatile("s_waitcnt vmcnt(%8)"
                                      : "+v"(rn[0]), "+v"(rn[1]), "+v"(rn[2]), "+v"(rn[3]), "+v"(rn[4]), "+v"(rn[5]), "+v"(rn[6]),
                                        "+v"(rn[7])
-                                     : "n"(FP8W ? 2 * HL + 8 : 3 * HL + 16));
+                                     : "n"(FP8W ? HL + 8 : 2 * HL + 16));
                     }
-                    piece(g, hh, 1, (pi + 1) * MB, cb, nb, 0);
-                    if (hh == SPG - 1) refill(g, s / SPG + g + 4);
+                    piece(g, hh, 1, (pi + 1) * MB, cb, nb, 0, [&](int y) {
+                        if (y < HL) load_h1(sl + 3 < NS ? sl + 3 : sl + 3 - NS, fb, y);
+                        else if (hh == SPG - 1 && y < HL + 4) refill1(g, L + 4, 2 * (y - HL));
+                    });
                     cb = nb;
                 }
             }
@@ -288,10 +311,10 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
         // (the lane's coordinates are derived again from an opaque copy of its index: values computed from them once, before
         // the tile loop, would have to live - in scratch memory - across the slab loop, and their reloads bring the
         // compiler's own waits for them into it)
-        int lane_e = lane;
-        asm volatile("" : "+v"(lane_e));
+        const int lane_e = lane_now();
         const int le16 = lane_e & 15, qe4 = lane_e >> 4;
-        // ---- lane (l16, q4) holds verify row 16y + l16 against vocabulary rows v0 + 16b + 4*q4 + r, ascending in (b, r)
+        // ---- lane (l16, q4) holds verify row 16y + l16 against vocabulary rows vb + 16b + 4*q4 + r, ascending in (b, r);
+        // those below v0 (a wave that starts early so as to stay inside the vocabulary) belong to another wave
 #pragma unroll
         for (int y = 0; y < MB; ++y) {
             const int row = y * 16 + le16, rowc = min(row, a.M - 1);
@@ -313,9 +336,9 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
             for (int b = 0; b < 4; ++b)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int v = v0 + b * 16 + qe4 * 4 + r;
+                    const int v = vb + b * 16 + qe4 * 4 + r;
                     float val = y < MBA ? acc[b][y < MBA ? y : 0][r] : accv[b][r];
-                    if (v < a.V) {
+                    if (v >= v0 && v < a.V) {
                         if (DUMP && row < a.M) a.dump[(size_t)row * a.V + v] = val;
                         if (SAMPLE) val = fmaf(val, a.inv_temp, gumbel_noise(klo, khi, (uint32_t)v));
                         if (val > bv) {      // strict >: the lowest index of the maximum
@@ -343,7 +366,7 @@ __global__ __launch_bounds__(WD_WAVES * 64) void k_lm_head_wide(LmHeadArgs a, in
             __builtin_amdgcn_sched_barrier(0);
         }
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        for (int row = threadIdx.x; row < MB * 16 && row < a.M; row += WD_WAVES * 64) {
+        for (int row = wave * 64 + lane_e; row < MB * 16 && row < a.M; row += WD_WAVES * 64) {
             Best best = red[0][row];
             int32_t cn = TOPK ? redc[0][row] : 0;
 #pragma unroll
@@ -400,7 +423,7 @@ bool lm_head_wide_supports(int M, int V, int d, bool fp8w)
 {
     // a trip of the slab loop covers 4 lines of a W_lm row: 256 k elements, 512 with FP8 weights
     const int trip = fp8w ? 512 : 256, wb = fp8w ? 1 : 2;
-    if (M <= 128 || M > WD_MAXB * 16 || V <= 0 || d < trip || d % trip != 0) return false;
+    if (M <= 128 || M > WD_MAXB * 16 || V < WD_N || d < trip || d % trip != 0) return false;
     if ((uint64_t)V * d * wb >= (1ull << 32) || (uint64_t)M * d * 2 >= (1ull << 32)) return false;
     return V < (1 << 24) && d * 2 < (1 << 24);
 }
