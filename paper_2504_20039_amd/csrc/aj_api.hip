@@ -118,7 +118,7 @@ static int plan_handle(const aj_config &c, aj_handle *h)
             h->variant = AJ_KERNEL_STREAM;
             h->stream16 = true;
             h->nblocks = lm_head_stream16_blocks(c.V, h->num_cus);
-        } else if (res) {
+        } else if (res && !(wide && h->M > 112 && c.kernel == AJ_KERNEL_AUTO)) {     // (113..128 rows: see the bf16 rule below)
             h->variant = AJ_KERNEL_RESIDENT;
             h->nblocks = lm_head_resident_blocks(c.V, h->num_cus);
         } else {
@@ -136,8 +136,8 @@ static int plan_handle(const aj_config &c, aj_handle *h)
         int v = c.kernel;
         if (v == AJ_KERNEL_AUTO) {
             // W_lm-streaming kernels up to 128 verify rows: the 16-row-tile kernel with hidden_t in registers
-            // (<= 32 rows, d_t = 2048 or 4096), else the kernel that keeps the logits in registers (d_t % 256 == 0), else
-            // 128-vocabulary tiles of 32, 64 or 128 rows with a running maximum.  129..272 rows: the wide kernel.
+            // (<= 32 rows, d_t = 2048 or 4096), else the kernel that keeps the logits in registers (d_t % 256 == 0, <= 112 rows), else
+            // 128-vocabulary tiles of 32, 64 or 128 rows with a running maximum.  113..272 rows: the wide kernel.
             // Above that, the large-tile kernel with the lowest cost = padded row count x a per-row factor against the
             // 256-row whole-line kernel (PAIR = 1).  Measured on 1056 rows at d_t = 4096 / 8192 and 8320 rows at 8192
             // (one device; devices differ by about 5 %): the 288-row variant 1.09 / 1.05 / 1.03, the 256-row kernel
@@ -147,12 +147,15 @@ static int plan_handle(const aj_config &c, aj_handle *h)
             // of 32.
             if (lm_head_stream16_supports(h->M, c.V, c.d_t)) {
                 v = AJ_KERNEL_STREAM;
-            } else if (lm_head_resident_supports(h->M, c.V, c.d_t, false)) {
-                v = AJ_KERNEL_RESIDENT;     // up to 128 rows at any hidden size that is a multiple of 256
+            } else if (h->M <= 112 && lm_head_resident_supports(h->M, c.V, c.d_t, false)) {
+                v = AJ_KERNEL_RESIDENT;     // up to 112 rows at any hidden size that is a multiple of 256
             } else if (lm_head_wide_supports(h->M, c.V, c.d_t, false)) {
-                // 129..272 rows: W_lm straight into registers, 16-row blocks, one row tile (0.37 ms against 0.46 of a padded
-                // 256-row tile at 144 rows of the 70B shape, 0.51 against 0.55 of the 288-row tile at 264)
+                // 113..272 rows: W_lm straight into registers, 16-row blocks, one row tile (0.37 ms against 0.46 of a padded
+                // 256-row tile at 144 rows of the 70B shape, 0.51 against 0.55 of the 288-row tile at 264; at 8 row blocks 0.36
+                // against the 0.40 of the accumulator-resident kernel, which is short of registers there)
                 v = AJ_KERNEL_WIDE;
+            } else if (lm_head_resident_supports(h->M, c.V, c.d_t, false)) {
+                v = AJ_KERNEL_RESIDENT;     // 113..128 rows where the wide kernel does not apply (a vocabulary under 256)
             } else if (lm_head_mfma_supports(AJ_KERNEL_STREAM, h->M, c.V, c.d_t)) {
                 v = AJ_KERNEL_STREAM;
             } else {

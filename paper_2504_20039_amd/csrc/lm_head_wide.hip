@@ -1,4 +1,4 @@
-// LM head (step 1) + per-vocabulary-block greedy maximum (first half of step 2) for 129..272 verify rows in ONE
+// LM head (step 1) + per-vocabulary-block greedy maximum (first half of step 2) for 113..272 verify rows in ONE
 // row tile (e.g. 8 windows x 33 rows = 264): 256 vocabulary rows x 16*MB verify rows per workgroup, MB <= 17 blocks
 // of v_mfma_f32_16x16x32_bf16, so that 264 rows pad to 272 (3 %) and W_lm is streamed from HBM exactly once.
 //
@@ -404,6 +404,7 @@ hipError_t dispatch_wide(const LmHeadArgs &a, int num_cus, hipStream_t s)
 {
     if (a.M <= 0) return hipSuccess;
     switch ((a.M + 15) / 16) {
+        case 8: return launch_wide<8, FP8W>(a, num_cus, s);
         case 9: return launch_wide<9, FP8W>(a, num_cus, s);
         case 10: return launch_wide<10, FP8W>(a, num_cus, s);
         case 11: return launch_wide<11, FP8W>(a, num_cus, s);
@@ -423,7 +424,7 @@ bool lm_head_wide_supports(int M, int V, int d, bool fp8w)
 {
     // a trip of the slab loop covers 4 lines of a W_lm row: 256 k elements, 512 with FP8 weights
     const int trip = fp8w ? 512 : 256, wb = fp8w ? 1 : 2;
-    if (M <= 128 || M > WD_MAXB * 16 || V < WD_N || d < trip || d % trip != 0) return false;
+    if (M <= 112 || M > WD_MAXB * 16 || V < WD_N || d < trip || d % trip != 0) return false;
     if ((uint64_t)V * d * wb >= (1ull << 32) || (uint64_t)M * d * 2 >= (1ull << 32)) return false;
     return V < (1 << 24) && d * 2 < (1 << 24);
 }

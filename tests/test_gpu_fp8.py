@@ -28,7 +28,7 @@ def fp8_case(w, seed, tau=None, repeat=1, sampled=None):
             return oracle.logits_row(x.ht[r], x.W) * sampled[0] + np.array([oracle.gumbel(int(keys[r]), v) for v in range(w.V)])
     rep = compare(x, draft, tau, greedy, gpu, scores_row=scores_row)
     assert gpu["kernel"] == ("lm_head_stream16_fp8w" if w.M <= 32 and w.d_t == 4096 else
-                             "lm_head_resident_fp8w" if w.M <= 128 else "lm_head_wide_fp8w")
+                             "lm_head_resident_fp8w" if w.M <= 112 or (w.M <= 128 and w.d_t % 512) else "lm_head_wide_fp8w")
     return rep, x, w8, gpu
 
 
@@ -39,7 +39,8 @@ def fp8_case(w, seed, tau=None, repeat=1, sampled=None):
     dict(B=3, K=7, V=70001),           # more tiles than workgroups: several per workgroup
     dict(B=1, K=32, V=5003, d_t=8192),     # 33 rows at the 70B hidden size: the accumulator-resident kernel
     dict(B=1, K=64, V=140000, d_t=1024),   # 65 rows; more vocabulary than one pass holds
-    dict(B=4, K=31, V=3000, d_t=512),      # 128 rows: all eight row blocks
+    dict(B=4, K=31, V=3000, d_t=768),      # 128 rows: all eight row blocks of the accumulator-resident kernel
+    dict(B=4, K=31, V=3000, d_t=512),      # 128 rows at a multiple of 512: the wide kernel's smallest tile
     dict(B=2, K=15, V=1000, d_t=2048),     # 32 rows at a hidden size the 16-row-tile kernel does not take in FP8
     dict(B=8, K=32, V=3000, d_t=1024),     # 264 rows: the wide kernel, 17 row blocks (the last one in VGPRs), ragged last tile
     dict(B=3, K=42, V=70001, d_t=512),     # 129 rows: 9 row blocks, one trip of the slab loop, more tiles than workgroups

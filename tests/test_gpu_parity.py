@@ -310,7 +310,7 @@ def test_profile_events_and_kernel_names():
     with pytest.raises(aj.AjError):
         aj.aj_profile_read(plain)
     aj.aj_destroy(plain)
-    for M_B, d_t, name in ((8, 4096, "lm_head_wide_bf16"), (8, 4096 + 64, "lm_head_big_bf16"), (4, 4096, "lm_head_resident_bf16"), (4, 4096 + 128, "lm_head_stream_bf16"), (5, 4096, "lm_head_wide_bf16"), (5, 4096 + 128, "lm_head_big_bf16"),
+    for M_B, d_t, name in ((8, 4096, "lm_head_wide_bf16"), (8, 4096 + 64, "lm_head_big_bf16"), (4, 4096, "lm_head_wide_bf16"), (3, 4096, "lm_head_resident_bf16"), (4, 4096 + 128, "lm_head_stream_bf16"), (5, 4096, "lm_head_wide_bf16"), (5, 4096 + 128, "lm_head_big_bf16"),
                            (4, 4096 + 8, "lm_head_tile_bf16"), (9, 4096, "lm_head_pair9_bf16"), (10, 4096, "lm_head_tall_bf16"),
                            (33, 4096, "lm_head_pair9_bf16"), (33, 4096 + 64, "lm_head_tall_bf16"),
                            (260, 4096, "lm_head_pair_bf16")):
