@@ -65,6 +65,9 @@ def test_tiny_f32_workload_with_all_logits():
     dict(B=8, K=32, d_t=1024, d_d=64, V=3000),         # M=264: 17 row blocks of the wide kernel (one in VGPRs)
     dict(B=3, K=42, d_t=256, d_d=64, V=70000),         # M=129: 9 row blocks, one trip of four slabs, 274 tiles on 256 workgroups
     dict(B=8, K=31, d_t=512, d_d=64, V=1000),          # M=256: 16 row blocks
+    dict(B=4, K=32, d_t=256, d_d=64, V=257),           # M=132, a second vocabulary tile of ONE row: every wave of it starts early
+    dict(B=4, K=29, d_t=512, d_d=64, V=256),           # M=120: the wide kernel's 8 row blocks, exactly one vocabulary tile
+    dict(B=6, K=31, d_t=256, d_d=64, V=319),           # M=192, 63 rows in the last tile: one wave with a range of its own
 ])
 def test_bf16_shapes_all_kernels(kernel, shape):
     import torch
