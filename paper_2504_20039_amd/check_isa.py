@@ -196,9 +196,9 @@ def check(hipcc, flags, verbose=False):
             want = (64 if fp8 else 32) * mb
             if sum("v_mfma" in l for l in loop) != want:
                 problems.append(f"{tag}: {sum('v_mfma' in l for l in loop)} MFMAs in the loop, expected {want}")
-            # the greedy instantiations of the smallest and the largest tile, one wave each of a workgroup with two tiles and
-            # of the one with the ragged last tile, through the address emulator
-            if mb in (8, 17) and m.group(3) == "0" and m.group(4) == "0" and m.group(5) == "0":
+            # the greedy, top-K and sampling instantiations of the smallest and the largest tile, one wave each of a workgroup
+            # with two tiles and of the one with the ragged last tile, through the address emulator
+            if mb in (8, 17) and m.group(3) == "0":
                 M, V, d = 16 * mb - 8, 66000 + 40, 1024
                 for wg, wave in ((0, 1), ((V + 255) // 256 - 1 - 256, 3)):
                     try:

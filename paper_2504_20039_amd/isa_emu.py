@@ -230,6 +230,20 @@ class Emu:
     def i_s_lshl3_add_u32(self, o, t): self.bin32(o, lambda a, b: (a << 3) + b, lambda a, b, r: int(r > M32))
     def i_s_lshl4_add_u32(self, o, t): self.bin32(o, lambda a, b: (a << 4) + b, lambda a, b, r: int(r > M32))
 
+    def un32(self, o, f):
+        a = self.sval(o[1])
+        self.s[o[0]] = None if a is None else f(a) & M32
+
+    def i_s_brev_b32(self, o, t): self.un32(o, lambda a: int('{:032b}'.format(a)[::-1], 2))
+    def i_s_not_b32(self, o, t):
+        self.un32(o, lambda a: ~a)
+        self.scc = None if self.s[o[0]] is None else int(self.s[o[0]] != 0)
+    def i_s_sext_i32_i16(self, o, t): self.un32(o, lambda a: ((a & 0xFFFF) ^ 0x8000) - 0x8000)
+    def i_s_sext_i32_i8(self, o, t): self.un32(o, lambda a: ((a & 0xFF) ^ 0x80) - 0x80)
+    def i_s_abs_i32(self, o, t):
+        self.un32(o, lambda a: abs(s32(a)))
+        self.scc = None if self.s[o[0]] is None else int(self.s[o[0]] != 0)
+
     def i_s_bfe_u32(self, o, t):
         self.bin32(o, lambda a, b: (a >> (b & 31)) & ((1 << ((b >> 16) & 0x7f)) - 1), lambda a, b, r: int((r & M32) != 0))
 
