@@ -138,12 +138,26 @@ def bench_workload(args, name, cache, cpu_seconds):
         for _ in range(10):
             step(h)
         torch.cuda.synchronize()
+    if args.graph:
+        # the step as a serving loop would issue it: captured once in a HIP graph (aj_verify only enqueues kernels),
+        # one graph launch per step
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step(h)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step(h)
+        timed_step = graph.replay
+    else:
+        timed_step = lambda: step(h)
     for _ in range(args.warmup):
-        step(h)
+        timed_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step(h)
+        timed_step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     accepted = out_len.cpu().numpy().astype(np.int64)
@@ -193,6 +207,7 @@ def bench_workload(args, name, cache, cpu_seconds):
                    "verify_rows": w.M, "tau": w.tau, "p_match": w.p_match, "seed": seed,
                    "draft_tokens": draft_from,
                    **({"w_dtype": "fp8_e4m3"} if fp8 else {}),
+                   **({"issued_as": "HIP graph replay"} if args.graph else {}),
                    **({"fused_judge": True} if args.fused_judge else {}),
                    **({"mode": "topk", "top_k": args.top_k} if topk else {}),
                    **({"mode": "sample", "inv_temperature": args.inv_temperature} if sample else {})},
@@ -253,6 +268,8 @@ def main():
                          "top-K lossy baseline on the same LM-head pass; sample: the judge-augmented step with "
                          "Gumbel-max sampled target tokens")
     ap.add_argument("--inv-temperature", type=float, default=1.0)
+    ap.add_argument("--graph", action="store_true",
+                    help="time the step as one HIP-graph launch (captured once) instead of the library call")
     ap.add_argument("--w-dtype", choices=["same", "fp8"], default="same",
                     help="fp8: W_lm stored as OCP FP8 E4M3; not the metric's configuration, which is bf16")
     ap.add_argument("--top-k", type=int, default=8)
